@@ -1,0 +1,160 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused log-prob + AIS + gradient path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch already resident in HBM:
+ais_token_logprob -> ais_diagnostics -> ais_grpo_loss_grad, back to back on one stream.
+Prints one JSON line (tokens/s = valid token rows per second), with the HBM roofline figures of the
+dominant kernel (the gradient sweep) and the CPU oracle timed on a bounded sample of the same batch.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E, vendor figure
+
+
+def cpu_baseline(batch, params, sample_rows: int):
+    """The CPU oracle, as it stands, on the first `sample_rows` rows of the batch (whole responses are
+    not needed: the sample is re-packed as responses of equal length so that every step of the path runs)."""
+    import numpy as np
+    import oracle.ais_oracle as O
+    from oracle.pool import OraclePool
+
+    shape = batch.shape
+    G = shape.group_size
+    n = min(sample_rows, batch.n_rows)
+    n -= n % G
+    per = n // G
+    z = batch.logits[:n]
+    dtype = shape.logits_dtype
+    bits = (z.view(__import__("torch").int16).cpu().numpy().view(np.uint16) if dtype == "bf16"
+            else z.cpu().numpy())
+    y = batch.token_ids[:n].cpu().numpy()
+    valid = batch.valid[:n].cpu().numpy()
+    lp_roll = batch.logp_roll[:n].double().cpu().numpy()
+    cu = np.arange(G + 1, dtype=np.int64) * per
+    rewards = np.array([1.0, 0.0] * (G // 2) + [1.0] * (G % 2))
+    workers = min(16, len(os.sched_getaffinity(0)))
+    pool = OraclePool(workers)
+    t0 = time.perf_counter()
+    out = pool.whole_path(bits, dtype, y, valid, cu, lp_roll, rewards, G, O.Params(**params))
+    dt = time.perf_counter() - t0
+    pool.close()
+    n_valid = int(valid.astype(bool).sum())
+    return {"value": n_valid / dt, "unit": "tokens/s", "cores": workers, "kind": "oracle",
+            "sample": f"first {n} rows ({n_valid} valid) of the same batch as {G} equal-length responses, "
+                      f"numpy fp64 oracle over {workers} worker processes, {dt:.2f} s wall"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = Qwen3-8B-shaped, V = 151,936)")
+    ap.add_argument("--cpu-rows", type=int, default=6144, help="rows of the batch the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--in-place", action="store_true", help="write the gradient over the logits")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the path has no inter-GPU step; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_13907_amd import binding, workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    shape = workloads.config(args.config)
+    t0 = time.perf_counter()
+    batch = workloads.generate(shape, "cuda", row_chunk=512)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t0
+    R, V = batch.logits.shape
+    N = batch.n_valid
+    e = batch.logits.element_size()
+    ctx = binding.AisContext()
+    p = binding.default_params()
+    dz = batch.logits if args.in_place else torch.empty_like(batch.logits)
+
+    def step():
+        logp, lse = ctx.token_logprob(batch.logits, batch.token_ids, batch.valid, p.inv_temperature)
+        adv, count, diag = ctx.diagnostics(logp, batch.logp_roll, batch.valid, batch.cu_rows, batch.rewards,
+                                           shape.group_size, p)
+        return ctx.grpo_loss_grad(batch.logits, batch.token_ids, batch.valid, batch.cu_rows, logp, lse,
+                                  batch.logp_roll, adv, count, diag, p, dlogits=dz), diag
+
+    if args.in_place:
+        keep = batch.logits.clone()
+
+    for _ in range(args.warmup):
+        step()
+        if args.in_place:
+            batch.logits.copy_(keep)
+    torch.cuda.synchronize()
+    ctx.profile(True)
+    t_total = 0.0
+    for _ in range(args.steps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        (loss, _, _), diag = step()
+        torch.cuda.synchronize()
+        t_total += time.perf_counter() - t0
+        if args.in_place:
+            batch.logits.copy_(keep)
+    ms_fwd, n_fwd = ctx.profile_read(binding.AIS_K_LOGPROB)
+    ms_bwd, n_bwd = ctx.profile_read(binding.AIS_K_DLOGITS)
+    ctx.profile(False)
+    d = ctx.read_diag(diag)
+    assert ctx.status() == 0
+
+    # plain copy of the logits: what this device's HBM sustains for a read+write stream
+    ctx.profile(True)
+    scratch = dz if not args.in_place else torch.empty_like(batch.logits)
+    for _ in range(3):
+        ctx.copy(scratch, batch.logits)
+    ms_copy, n_copy = ctx.profile_read(binding.AIS_K_COPY)
+    ctx.profile(False)
+    copy_gbps = 2.0 * R * V * e / (ms_copy / n_copy * 1e-3) / 1e9
+
+    ms_step = t_total / args.steps * 1e3
+    fwd_bytes = e * V * N                                   # one read of every valid row
+    bwd_bytes = 2 * e * V * N + e * V * (R - N)             # read + write of valid rows, zero-fill of the others
+    fwd_gbps = fwd_bytes / (ms_fwd / n_fwd * 1e-3) / 1e9
+    bwd_gbps = bwd_bytes / (ms_bwd / n_bwd * 1e-3) / 1e9
+    path_gbps = (fwd_bytes + bwd_bytes) / (ms_step * 1e-3) / 1e9
+    result = {
+        "metric": "fused_logprob_ais_grad_tokens_per_s", "value": N / (ms_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if shape.logits_dtype == "f32" else "f32 (bf16 storage)", "data": "synthetic",
+        "config": {"workload": f"config {args.config}: {shape.name}", "vocab": V, "rows": R, "valid_rows": N,
+                   "responses": shape.n_resp, "group_size": shape.group_size, "logits": shape.logits_dtype,
+                   "layout": shape.layout, "in_place": bool(args.in_place)},
+        "roofline": {"bound": "hbm", "kernel": "dlogits_kernel", "achieved": bwd_gbps, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": bwd_gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "avg_ms": ms_bwd / n_bwd, "bytes_per_launch": bwd_bytes},
+        "kernels": {"token_logprob": {"avg_ms": ms_fwd / n_fwd, "GB/s": fwd_gbps, "frac": fwd_gbps / HBM_PEAK_GBPS},
+                    "dlogits": {"avg_ms": ms_bwd / n_bwd, "GB/s": bwd_gbps, "frac": bwd_gbps / HBM_PEAK_GBPS},
+                    "copy_yardstick": {"avg_ms": ms_copy / n_copy, "GB/s": copy_gbps}},
+        "path_hbm": {"GB/s": path_gbps, "frac": path_gbps / HBM_PEAK_GBPS,
+                     "bytes_per_step": fwd_bytes + bwd_bytes},
+        "diag": {k: d[k] for k in ("alpha", "alpha_ess", "alpha_mis", "alpha_var", "dbar", "ess_ratio")},
+        "loss": float(loss.item()), "gen_s": t_gen,
+    }
+    if args.cpu_rows > 0:
+        params = dict(C=p.C, delta=p.delta, gamma=p.gamma, eps_std=p.eps_std, beta_var=p.beta_var,
+                      clip_eps=p.clip_eps)
+        result["cpu_baseline"] = cpu_baseline(batch, params, args.cpu_rows)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

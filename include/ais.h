@@ -1,0 +1,208 @@
+/*
+ * ais.h — C ABI of the AIS-GRPO hot path on one AMD MI355X (gfx950).
+ *
+ * The library evaluates, for one batch of rollouts, the part of an AIS-GRPO
+ * training step that lies between the trainer's forward pass and its backward
+ * pass (Alg. 1, "Adaptive Coefficient Estimation", "Advantage Rectification"
+ * and the objective of Eq. 19):
+ *
+ *   ais_token_logprob    log pi_train(o_t) for every evaluated token, from the
+ *                        full-vocabulary trainer logits
+ *   ais_diagnostics      sampler-trainer ratios, the three diagnostics
+ *                        (Eq. 12, 14, 16), the mixing coefficient alpha
+ *                        (Eq. 17), group-relative advantages (Eq. 3)
+ *   ais_grpo_loss_grad   rectification weights (Eq. 18), the AIS-GRPO loss
+ *                        (Eq. 19, negated) and its gradient w.r.t. the logits
+ *
+ * Conventions that hold for every call
+ *   Memory     Every array argument is DEVICE memory owned by the caller on the
+ *              context's GPU, unless its comment says "host".  Nothing is kept
+ *              after a call returns; the context owns only a small reduction
+ *              workspace.  Outputs must not overlap inputs unless stated.
+ *   Order      Calls enqueue work on the context's HIP stream and return
+ *              without waiting for it.  Results are ready when that stream
+ *              reaches the point of the call.  Calls on one context must not
+ *              overlap in time (they share its workspace).
+ *   Layout     Logits are row-major [n_rows, vocab] with a row pitch of
+ *              row_stride elements.  One row is one token position.  Response
+ *              i owns rows [cu_rows[i], cu_rows[i+1]); cu_rows[0] = 0,
+ *              cu_rows[n_resp] = n_rows, non-decreasing.  Prompt p owns the
+ *              group_size consecutive responses starting at p * group_size.
+ *              valid[n] != 0 marks a row whose token is evaluated (a generated,
+ *              non-padding position; for masked-diffusion rollouts a masked
+ *              position).  valid == NULL means all rows.
+ *   Errors     Functions return 0 on success or a negative ais_error.
+ *              Arguments are checked on the host before anything is launched;
+ *              a failing call launches nothing.  Faults that only the device
+ *              can see (a token id outside [0, vocab) on an evaluated row,
+ *              cu_rows that is not a partition of the rows) never cause an
+ *              out-of-range access: the row is computed as if it had no token
+ *              (its logp is 0), and a bit is set in the context's status word
+ *              (ais_status) and in ais_diag.status.
+ *   Degenerate n_rows = 0, no valid row at all, a response without valid rows,
+ *              all rewards equal: not errors; outputs are 0 and alpha = 0.
+ */
+#ifndef AIS_H_
+#define AIS_H_
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ais_ctx ais_ctx;
+
+typedef enum ais_dtype { AIS_BF16 = 0, AIS_F32 = 1 } ais_dtype;
+
+typedef enum ais_error {
+  AIS_OK = 0,
+  AIS_ERR_NULL = -1,    /* a required pointer is NULL                                  */
+  AIS_ERR_SIZE = -2,    /* a negative or zero size where one is not allowed, or > limit  */
+  AIS_ERR_STRIDE = -3,  /* row_stride < vocab                                          */
+  AIS_ERR_ALIGN = -4,   /* a pointer is not aligned to its element type                */
+  AIS_ERR_PARAM = -5,   /* a hyper-parameter outside its domain                        */
+  AIS_ERR_GROUP = -6,   /* n_resp is not a positive multiple of group_size             */
+  AIS_ERR_DTYPE = -7,   /* unknown ais_dtype                                           */
+  AIS_ERR_HIP = -8,     /* a HIP runtime call failed (see ais_last_hip_error)          */
+  AIS_ERR_NOMEM = -9    /* workspace allocation failed                                 */
+} ais_error;
+
+/* Bits of the device status word. */
+#define AIS_STATUS_BAD_TOKEN 1   /* evaluated row with token id outside [0, vocab)     */
+#define AIS_STATUS_BAD_CU    2   /* cu_rows not a non-decreasing partition of the rows */
+
+/* Hyper-parameters.  ais_params_default() fills in the paper's values:
+ * C, delta, gamma, eps_std from App. "AIS hyperparameters"; clip_eps from the
+ * hyper-parameter table of App. "RL Training Setup". */
+typedef struct ais_params {
+  float C;               /* 5.0   truncation of the importance ratio, >= 1 (Eq. 10)            */
+  float delta;           /* 0.02  saturation threshold of alpha_mis, > 0 (Eq. 14)              */
+  float gamma;           /* 1.2   variance tolerance of alpha_var, > 0 (Eq. 16)                */
+  float eps_std;         /* 1e-6  stabiliser in the variance-amplification ratio (Eq. 15)      */
+  float beta_var;        /* 1.0   beta of Eq. 17; the paper prints no value                    */
+  float clip_eps;        /* 0.2   PPO clipping range of Eq. 19, in [0, 1)                      */
+  int   adv_mode;        /* 0: A = r - mean(group) (Eq. 3);  1: divided by (pstd(group)+eps)  */
+  float alpha_override;  /* < 0: adaptive alpha (Eq. 17); in [0,1]: forced (0 = plain GRPO,
+                            1 = token-level truncated importance sampling, Eq. 8)              */
+  float inv_temperature; /* 1.0   logits are multiplied by this before the softmax, > 0        */
+  float beta_kl;         /* 0.0   weight of the KL term of Eq. 19 (needs logp_ref), >= 0       */
+} ais_params;
+
+/* Written by ais_diagnostics into DEVICE memory; statistics are over the valid
+ * rows of the batch (population moments, A broadcast to the tokens of its response). */
+typedef struct ais_diag {
+  long long n_valid;     /* number of valid rows                                               */
+  double mean_w, var_w;  /* mean and population variance of w_bar = min(rho, C)                */
+  double cv2;            /* squared coefficient of variation of w_bar                          */
+  double ess_ratio;      /* 1 / (1 + cv2)                                                      */
+  double dbar;           /* mean |log pi_train - log pi_roll|            (Eq. 13)              */
+  double std_a, std_aw;  /* population std of A and of A * w_bar                               */
+  double dsigma;         /* std_aw / (std_a + eps_std)                    (Eq. 15)             */
+  double alpha_ess;      /* (1 + cv2)^(-1/2)                              (Eq. 12)             */
+  double alpha_mis;      /* min(1, dbar / delta)                          (Eq. 14)             */
+  double alpha_var;      /* max(0, (dsigma - gamma) / gamma)              (Eq. 16)             */
+  double alpha;          /* clip(alpha_ess - beta_var alpha_var, 0, 1) alpha_mis (Eq. 17),
+                            or alpha_override                                                  */
+  double clip_frac;      /* share of valid rows with rho > C                                   */
+  int status;            /* the context's status word at the time of the call                 */
+  int reserved;
+} ais_diag;
+
+/* ---- context ------------------------------------------------------------------------------ */
+
+/* Creates a context on GPU `device` that launches on `hip_stream` (a hipStream_t; NULL = the
+ * default stream).  *out is host memory.  Allocates a small device workspace. */
+int ais_create(ais_ctx** out, int device, void* hip_stream);
+/* Waits for the context's stream, frees the workspace.  NULL is allowed. */
+int ais_destroy(ais_ctx* ctx);
+/* Changes the stream later calls launch on. */
+int ais_set_stream(ais_ctx* ctx, void* hip_stream);
+/* Writes the paper's defaults into *p (host memory). */
+void ais_params_default(ais_params* p);
+/* Static, NUL-terminated description of an ais_error. */
+const char* ais_strerror(int err);
+/* hipError_t of the last failing HIP call on this context (0 if none). */
+int ais_last_hip_error(const ais_ctx* ctx);
+/* Waits for the stream, copies the device status word to *host_out, and clears it if `clear`. */
+int ais_status(ais_ctx* ctx, int* host_out, int clear);
+/* Library version, major * 1000 + minor. */
+int ais_version(void);
+
+/* ---- the three calls of the path ------------------------------------------------------------ */
+
+/* log pi_train(o_t): one streaming pass over each valid row (Alg. 1, "Compute full-precision
+ * log-probs ... for all generated tokens").
+ *   logits      [n_rows, row_stride] of `dtype`; read once; rows with valid == 0 are not read
+ *   token_ids   [n_rows] sampled token per row; ignored (never read) where valid == 0
+ *   logp_out    [n_rows] fp32  inv_temperature * z[n, y_n] - lse_n;  0 where valid == 0
+ *   lse_out     [n_rows] fp32  log sum_v exp(inv_temperature * z[n, v]);  0 where valid == 0
+ * Any vocab >= 1 and any row_stride >= vocab are accepted; 16-byte vector loads are used when
+ * the base pointer and the row pitch allow it, an element-wise path otherwise.
+ * Errors: NULL logits/token_ids/logp_out/lse_out (with n_rows > 0), n_rows < 0, vocab < 1,
+ * vocab >= 2^31, row_stride < vocab, inv_temperature <= 0 or not finite, unknown dtype,
+ * logits not aligned to its element size. */
+int ais_token_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows,
+                      long long vocab, long long row_stride, const int* token_ids,
+                      const unsigned char* valid, float inv_temperature, float* logp_out,
+                      float* lse_out);
+
+/* Ratios, diagnostics and alpha (Alg. 1, "Sampler-Trainer ratio" to "Bilateral gating";
+ * Eq. 7, 10, 12-17), plus the group-relative advantages (Eq. 3).
+ *   logp_train, logp_roll  [n_rows] fp32
+ *   cu_rows     [n_resp + 1] int64 row offsets of the responses
+ *   rewards     [n_resp] fp32
+ *   adv_out     [n_resp] fp32   A_i
+ *   count_out   [n_resp] int32  |o_i| = number of valid rows of response i
+ *   diag_out    one ais_diag in device memory
+ * Errors: NULL pointers (valid may be NULL), n_rows < 0, n_resp < 1, group_size < 1,
+ * n_resp % group_size != 0, C < 1, delta <= 0, gamma <= 0, eps_std < 0, alpha_override > 1,
+ * adv_mode not in {0, 1}. */
+int ais_diagnostics(ais_ctx* ctx, const float* logp_train, const float* logp_roll,
+                    const unsigned char* valid, long long n_rows, const long long* cu_rows,
+                    int n_resp, int group_size, const float* rewards, const ais_params* params,
+                    float* adv_out, int* count_out, ais_diag* diag_out);
+
+/* Loss and gradient (Alg. 1, "Advantage Rectification" and "Policy Update"; Eq. 18, 19).
+ * With w_bar = min(exp(logp_train - logp_roll), C), w_tilde = 1 + alpha (w_bar - 1) and
+ * rho_on = exp(logp_train - logp_old) (1 if logp_old is NULL):
+ *   loss = -(1/n_resp) sum_i (1/|o_i|) sum_{valid t in i}
+ *              [ w_tilde min(rho_on A_i, clip(rho_on, 1 -+ clip_eps) A_i) - beta_kl k3_t ]
+ *   dlogits[n, v] = g_n * inv_temperature * (softmax(inv_temperature z_n)_v - 1[v = y_n])
+ * where g_n is the derivative of that row's term w.r.t. its log-probability (zero when the
+ * clipped branch is the minimum), alpha / w_tilde / A being constants, and
+ * k3 = exp(q) - q - 1, q = logp_ref - logp_train (used only if logp_ref != NULL and beta_kl > 0).
+ *   logits, token_ids, valid, cu_rows   as above (the same arrays given to the first two calls)
+ *   logp_train, lse   outputs of ais_token_logprob;  adv, count, diag  outputs of ais_diagnostics
+ *   logp_old, logp_ref   [n_rows] fp32 or NULL
+ *   wtilde_out  [n_rows] fp32 (0 where valid == 0); may be NULL
+ *   loss_out    one double in device memory
+ *   dlogits     [n_rows, row_stride] of `dtype`, same pitch as logits; every element of the
+ *               first `vocab` columns is written (0 on rows without gradient); bf16 results
+ *               are rounded to nearest even.  May be the same buffer as `logits` (in place).
+ * Errors: as for the first two calls. */
+int ais_grpo_loss_grad(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows,
+                       long long vocab, long long row_stride, const int* token_ids,
+                       const unsigned char* valid, const long long* cu_rows, int n_resp,
+                       const float* logp_train, const float* lse, const float* logp_roll,
+                       const float* logp_old, const float* logp_ref, const float* adv,
+                       const int* count, const ais_diag* diag, const ais_params* params,
+                       float* wtilde_out, double* loss_out, void* dlogits);
+
+/* ---- measurement helpers -------------------------------------------------------------------- */
+
+/* Kernels whose device time can be read back. */
+typedef enum ais_kernel { AIS_K_LOGPROB = 0, AIS_K_DLOGITS = 1, AIS_K_COPY = 2, AIS_K_COUNT_ = 3 } ais_kernel;
+
+/* With `enable` != 0 every launch of the kernels above is bracketed by HIP events on the
+ * context's stream; enabling also clears what was gathered before. */
+int ais_profile(ais_ctx* ctx, int enable);
+/* Waits for the stream; *total_ms (host) = summed event time of kernel `which`, *launches (host)
+ * = number of launches measured since profiling was enabled. */
+int ais_profile_read(ais_ctx* ctx, int which, float* total_ms, int* launches);
+/* Plain device-to-device copy kernel of `bytes` bytes (a multiple of 16, both pointers 16-byte
+ * aligned): the yardstick for achievable HBM bandwidth and for scaling hardware counters. */
+int ais_copy(ais_ctx* ctx, void* dst, const void* src, long long bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AIS_H_ */

@@ -1,0 +1,85 @@
+// Internal declarations shared by the translation units of the library (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "ais.h"
+
+namespace ais {
+
+constexpr int kSweepThreads = 256;     // one workgroup (4 wavefronts) streams one logits row
+constexpr int kTileThreads = 256;      // workgroup of the per-row scalar kernels
+constexpr int kTileRows = 1024;        // rows of one response handled by one such workgroup
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Per-tile partial sums of the diagnostics reduction (level 1 -> level 2).
+struct DiagPartial {
+  double su;      // sum of (w_bar - 1)
+  double su2;     // sum of (w_bar - 1)^2
+  double sabs;    // sum of |log pi_train - log pi_roll|
+  long long cnt;  // valid rows
+  long long nclip;  // rows with rho > C
+};
+
+// Byte offsets of the regions of the context workspace for a call with (n_rows, n_resp).
+struct WorkspaceLayout {
+  size_t tile_off;   // int [n_resp + 1]   first tile of each response
+  size_t partial;    // DiagPartial [max_tiles]  (reused as double [max_tiles] by the loss)
+  size_t g;          // float [n_rows]     per-row gradient coefficient
+  size_t total;
+  int max_tiles;
+};
+WorkspaceLayout workspace_layout(long long n_rows, int n_resp);
+
+}  // namespace ais
+
+struct ais_ctx {
+  int device = 0;
+  hipStream_t stream = nullptr;
+  void* ws = nullptr;
+  size_t ws_bytes = 0;
+  int* status_dev = nullptr;
+  int last_hip_error = 0;
+  bool profiling = false;
+  struct Timed { hipEvent_t start, stop; int which; };
+  std::vector<Timed> timed;      // events of measured launches
+  std::vector<hipEvent_t> pool;  // recycled events
+};
+
+namespace ais {
+
+int ensure_workspace(ais_ctx* ctx, size_t bytes);
+int hip_fail(ais_ctx* ctx, hipError_t e);
+
+// Brackets one launch with events when profiling is on.
+struct ScopedTimer {
+  ais_ctx* ctx;
+  int idx = -1;
+  ScopedTimer(ais_ctx* c, int which);
+  ~ScopedTimer();
+};
+
+// Launchers (each checks nothing: arguments were validated by the entry point).
+int launch_token_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,
+                         long long row_stride, const int* token_ids, const unsigned char* valid,
+                         float inv_temperature, float* logp_out, float* lse_out);
+int launch_dlogits(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,
+                   long long row_stride, const int* token_ids, const float* g, const float* lse,
+                   const float* logp, float inv_temperature, void* dlogits);
+int launch_plan(ais_ctx* ctx, const long long* cu_rows, int n_resp, long long n_rows, int* tile_off, int max_tiles);
+int launch_diagnostics(ais_ctx* ctx, const float* logp_train, const float* logp_roll, const unsigned char* valid,
+                       long long n_rows, const long long* cu_rows, int n_resp, int group_size,
+                       const float* rewards, const ais_params& p, const int* tile_off, int max_tiles,
+                       DiagPartial* partial, float* adv_out, int* count_out, ais_diag* diag_out);
+int launch_row_coeff(ais_ctx* ctx, const float* logp_train, const float* logp_roll, const float* logp_old,
+                     const float* logp_ref, const unsigned char* valid, long long n_rows,
+                     const long long* cu_rows, int n_resp, const float* adv, const int* count,
+                     const ais_diag* diag, const ais_params& p, const int* tile_off, int max_tiles,
+                     double* partial, float* g_out, float* wtilde_out, double* loss_out);
+int launch_copy(ais_ctx* ctx, void* dst, const void* src, long long bytes);
+
+}  // namespace ais

@@ -1,0 +1,326 @@
+// The C entry points: host-side argument checks, workspace, launches.  See include/ais.h for the contract.
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "ais_internal.h"
+
+namespace ais {
+
+int hip_fail(ais_ctx* ctx, hipError_t e) {
+  if (e == hipSuccess) return AIS_OK;
+  if (ctx != nullptr) ctx->last_hip_error = (int)e;
+  return AIS_ERR_HIP;
+}
+
+int ensure_workspace(ais_ctx* ctx, size_t bytes) {
+  if (bytes <= ctx->ws_bytes) return AIS_OK;
+  // growing is rare (first call at a new size); it waits for queued work that may still use the old block
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  if (ctx->ws != nullptr) {
+    (void)hipFree(ctx->ws);
+    ctx->ws = nullptr;
+    ctx->ws_bytes = 0;
+  }
+  const size_t want = bytes + bytes / 4;
+  e = hipMalloc(&ctx->ws, want);
+  if (e != hipSuccess) {
+    ctx->last_hip_error = (int)e;
+    (void)hipGetLastError();
+    return AIS_ERR_NOMEM;
+  }
+  ctx->ws_bytes = want;
+  return AIS_OK;
+}
+
+ScopedTimer::ScopedTimer(ais_ctx* c, int which) : ctx(c) {
+  if (!ctx->profiling) return;
+  ais_ctx::Timed t;
+  t.which = which;
+  hipEvent_t* ev[2] = {&t.start, &t.stop};
+  for (auto* e : ev) {
+    if (!ctx->pool.empty()) {
+      *e = ctx->pool.back();
+      ctx->pool.pop_back();
+    } else if (hipEventCreate(e) != hipSuccess) {
+      return;
+    }
+  }
+  (void)hipEventRecord(t.start, ctx->stream);
+  ctx->timed.push_back(t);
+  idx = (int)ctx->timed.size() - 1;
+}
+ScopedTimer::~ScopedTimer() {
+  if (idx >= 0) (void)hipEventRecord(ctx->timed[idx].stop, ctx->stream);
+}
+
+namespace {
+
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = true;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+    if (prev != dev) ok = (hipSetDevice(dev) == hipSuccess);
+  }
+  ~DeviceGuard() {
+    if (prev >= 0) (void)hipSetDevice(prev);
+  }
+};
+
+int check_logits(const void* logits, ais_dtype dtype, long long n_rows, long long vocab, long long row_stride) {
+  if (dtype != AIS_BF16 && dtype != AIS_F32) return AIS_ERR_DTYPE;
+  if (n_rows < 0 || n_rows > 0x7fffffffLL) return AIS_ERR_SIZE;
+  if (vocab < 1 || vocab > 0x7fffffffLL - 8) return AIS_ERR_SIZE;
+  if (row_stride < vocab) return AIS_ERR_STRIDE;
+  if (n_rows > 0 && logits == nullptr) return AIS_ERR_NULL;
+  const size_t esize = dtype == AIS_BF16 ? 2 : 4;
+  if (reinterpret_cast<uintptr_t>(logits) % esize != 0) return AIS_ERR_ALIGN;
+  return AIS_OK;
+}
+
+int check_params(const ais_params* p) {
+  if (p == nullptr) return AIS_ERR_NULL;
+  auto fin = [](float v) { return std::isfinite(v); };
+  if (!fin(p->C) || p->C < 1.f) return AIS_ERR_PARAM;
+  if (!fin(p->delta) || p->delta <= 0.f) return AIS_ERR_PARAM;
+  if (!fin(p->gamma) || p->gamma <= 0.f) return AIS_ERR_PARAM;
+  if (!fin(p->eps_std) || p->eps_std < 0.f) return AIS_ERR_PARAM;
+  if (!fin(p->beta_var) || p->beta_var < 0.f) return AIS_ERR_PARAM;
+  if (!fin(p->clip_eps) || p->clip_eps < 0.f || p->clip_eps >= 1.f) return AIS_ERR_PARAM;
+  if (p->adv_mode != 0 && p->adv_mode != 1) return AIS_ERR_PARAM;
+  if (std::isnan(p->alpha_override) || p->alpha_override > 1.f) return AIS_ERR_PARAM;
+  if (!fin(p->inv_temperature) || p->inv_temperature <= 0.f) return AIS_ERR_PARAM;
+  if (!fin(p->beta_kl) || p->beta_kl < 0.f) return AIS_ERR_PARAM;
+  return AIS_OK;
+}
+
+int check_batch(long long n_rows, int n_resp, int group_size) {
+  if (n_rows < 0 || n_rows > 0x7fffffffLL) return AIS_ERR_SIZE;
+  if (n_resp < 1 || n_resp > (1 << 24)) return AIS_ERR_SIZE;
+  if (group_size < 1) return AIS_ERR_SIZE;
+  if (n_resp % group_size != 0) return AIS_ERR_GROUP;
+  return AIS_OK;
+}
+
+}  // namespace
+}  // namespace ais
+
+using namespace ais;
+
+extern "C" {
+
+int ais_version(void) { return 1000; }
+
+void ais_params_default(ais_params* p) {
+  if (p == nullptr) return;
+  p->C = 5.0f;
+  p->delta = 0.02f;
+  p->gamma = 1.2f;
+  p->eps_std = 1e-6f;
+  p->beta_var = 1.0f;
+  p->clip_eps = 0.2f;
+  p->adv_mode = 0;
+  p->alpha_override = -1.0f;
+  p->inv_temperature = 1.0f;
+  p->beta_kl = 0.0f;
+}
+
+const char* ais_strerror(int err) {
+  switch (err) {
+    case AIS_OK: return "ok";
+    case AIS_ERR_NULL: return "a required pointer is NULL";
+    case AIS_ERR_SIZE: return "a size is negative, zero or too large";
+    case AIS_ERR_STRIDE: return "row_stride is smaller than vocab";
+    case AIS_ERR_ALIGN: return "a pointer is not aligned to its element type";
+    case AIS_ERR_PARAM: return "a hyper-parameter is outside its domain";
+    case AIS_ERR_GROUP: return "n_resp is not a multiple of group_size";
+    case AIS_ERR_DTYPE: return "unknown logits dtype";
+    case AIS_ERR_HIP: return "a HIP runtime call failed";
+    case AIS_ERR_NOMEM: return "workspace allocation failed";
+    default: return "unknown error";
+  }
+}
+
+int ais_create(ais_ctx** out, int device, void* hip_stream) {
+  if (out == nullptr) return AIS_ERR_NULL;
+  *out = nullptr;
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || device < 0 || device >= n_dev) {
+    (void)hipGetLastError();
+    return AIS_ERR_HIP;
+  }
+  ais_ctx* ctx = new (std::nothrow) ais_ctx;
+  if (ctx == nullptr) return AIS_ERR_NOMEM;
+  ctx->device = device;
+  ctx->stream = static_cast<hipStream_t>(hip_stream);
+  DeviceGuard guard(device);
+  hipError_t e = guard.ok ? hipMalloc(reinterpret_cast<void**>(&ctx->status_dev), 256) : hipErrorInvalidDevice;
+  if (e == hipSuccess) e = hipMemset(ctx->status_dev, 0, 256);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    delete ctx;
+    return AIS_ERR_HIP;
+  }
+  int rc = ensure_workspace(ctx, 1 << 20);
+  if (rc != AIS_OK) {
+    (void)hipFree(ctx->status_dev);
+    delete ctx;
+    return rc;
+  }
+  *out = ctx;
+  return AIS_OK;
+}
+
+int ais_destroy(ais_ctx* ctx) {
+  if (ctx == nullptr) return AIS_OK;
+  DeviceGuard guard(ctx->device);
+  (void)hipStreamSynchronize(ctx->stream);
+  for (auto& t : ctx->timed) {
+    (void)hipEventDestroy(t.start);
+    (void)hipEventDestroy(t.stop);
+  }
+  for (auto& e : ctx->pool) (void)hipEventDestroy(e);
+  if (ctx->ws != nullptr) (void)hipFree(ctx->ws);
+  if (ctx->status_dev != nullptr) (void)hipFree(ctx->status_dev);
+  delete ctx;
+  return AIS_OK;
+}
+
+int ais_set_stream(ais_ctx* ctx, void* hip_stream) {
+  if (ctx == nullptr) return AIS_ERR_NULL;
+  ctx->stream = static_cast<hipStream_t>(hip_stream);
+  return AIS_OK;
+}
+
+int ais_last_hip_error(const ais_ctx* ctx) { return ctx == nullptr ? 0 : ctx->last_hip_error; }
+
+int ais_status(ais_ctx* ctx, int* host_out, int clear) {
+  if (ctx == nullptr || host_out == nullptr) return AIS_ERR_NULL;
+  DeviceGuard guard(ctx->device);
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (e == hipSuccess) e = hipMemcpy(host_out, ctx->status_dev, sizeof(int), hipMemcpyDeviceToHost);
+  if (e == hipSuccess && clear) e = hipMemset(ctx->status_dev, 0, sizeof(int));
+  return hip_fail(ctx, e);
+}
+
+int ais_token_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, long long vocab,
+                      long long row_stride, const int* token_ids, const unsigned char* valid,
+                      float inv_temperature, float* logp_out, float* lse_out) {
+  int rc = check_logits(logits, dtype, n_rows, vocab, row_stride);
+  if (rc != AIS_OK) return rc;
+  if (n_rows > 0 && (token_ids == nullptr || logp_out == nullptr || lse_out == nullptr)) return AIS_ERR_NULL;
+  if (!std::isfinite(inv_temperature) || inv_temperature <= 0.f) return AIS_ERR_PARAM;
+  if (ctx == nullptr) return AIS_ERR_NULL;
+  DeviceGuard guard(ctx->device);
+  return launch_token_logprob(ctx, logits, dtype, n_rows, (int)vocab, row_stride, token_ids, valid,
+                              inv_temperature, logp_out, lse_out);
+}
+
+int ais_diagnostics(ais_ctx* ctx, const float* logp_train, const float* logp_roll, const unsigned char* valid,
+                    long long n_rows, const long long* cu_rows, int n_resp, int group_size,
+                    const float* rewards, const ais_params* params, float* adv_out, int* count_out,
+                    ais_diag* diag_out) {
+  int rc = check_batch(n_rows, n_resp, group_size);
+  if (rc != AIS_OK) return rc;
+  rc = check_params(params);
+  if (rc != AIS_OK) return rc;
+  if (cu_rows == nullptr || rewards == nullptr || adv_out == nullptr || count_out == nullptr ||
+      diag_out == nullptr)
+    return AIS_ERR_NULL;
+  if (n_rows > 0 && (logp_train == nullptr || logp_roll == nullptr)) return AIS_ERR_NULL;
+  if (ctx == nullptr) return AIS_ERR_NULL;
+  DeviceGuard guard(ctx->device);
+  const WorkspaceLayout w = workspace_layout(n_rows, n_resp);
+  rc = ensure_workspace(ctx, w.total);
+  if (rc != AIS_OK) return rc;
+  char* ws = static_cast<char*>(ctx->ws);
+  int* tile_off = reinterpret_cast<int*>(ws + w.tile_off);
+  rc = launch_plan(ctx, cu_rows, n_resp, n_rows, tile_off, w.max_tiles);
+  if (rc != AIS_OK) return rc;
+  return launch_diagnostics(ctx, logp_train, logp_roll, valid, n_rows, cu_rows, n_resp, group_size, rewards,
+                            *params, tile_off, w.max_tiles, reinterpret_cast<DiagPartial*>(ws + w.partial),
+                            adv_out, count_out, diag_out);
+}
+
+int ais_grpo_loss_grad(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, long long vocab,
+                       long long row_stride, const int* token_ids, const unsigned char* valid,
+                       const long long* cu_rows, int n_resp, const float* logp_train, const float* lse,
+                       const float* logp_roll, const float* logp_old, const float* logp_ref, const float* adv,
+                       const int* count, const ais_diag* diag, const ais_params* params, float* wtilde_out,
+                       double* loss_out, void* dlogits) {
+  int rc = check_logits(logits, dtype, n_rows, vocab, row_stride);
+  if (rc != AIS_OK) return rc;
+  rc = check_batch(n_rows, n_resp, 1);
+  if (rc != AIS_OK) return rc;
+  rc = check_params(params);
+  if (rc != AIS_OK) return rc;
+  if (cu_rows == nullptr || adv == nullptr || count == nullptr || diag == nullptr || loss_out == nullptr)
+    return AIS_ERR_NULL;
+  if (n_rows > 0 && (token_ids == nullptr || logp_train == nullptr || lse == nullptr || logp_roll == nullptr ||
+                     dlogits == nullptr))
+    return AIS_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(dlogits) % (dtype == AIS_BF16 ? 2 : 4) != 0) return AIS_ERR_ALIGN;
+  if (ctx == nullptr) return AIS_ERR_NULL;
+  DeviceGuard guard(ctx->device);
+  const WorkspaceLayout w = workspace_layout(n_rows, n_resp);
+  rc = ensure_workspace(ctx, w.total);
+  if (rc != AIS_OK) return rc;
+  char* ws = static_cast<char*>(ctx->ws);
+  int* tile_off = reinterpret_cast<int*>(ws + w.tile_off);
+  float* g = reinterpret_cast<float*>(ws + w.g);
+  rc = launch_plan(ctx, cu_rows, n_resp, n_rows, tile_off, w.max_tiles);
+  if (rc != AIS_OK) return rc;
+  rc = launch_row_coeff(ctx, logp_train, logp_roll, logp_old, logp_ref, valid, n_rows, cu_rows, n_resp, adv, count,
+                        diag, *params, tile_off, w.max_tiles, reinterpret_cast<double*>(ws + w.partial), g,
+                        wtilde_out, loss_out);
+  if (rc != AIS_OK) return rc;
+  return launch_dlogits(ctx, logits, dtype, n_rows, (int)vocab, row_stride, token_ids, g, lse, logp_train,
+                        params->inv_temperature, dlogits);
+}
+
+int ais_profile(ais_ctx* ctx, int enable) {
+  if (ctx == nullptr) return AIS_ERR_NULL;
+  DeviceGuard guard(ctx->device);
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  for (auto& t : ctx->timed) {
+    ctx->pool.push_back(t.start);
+    ctx->pool.push_back(t.stop);
+  }
+  ctx->timed.clear();
+  ctx->profiling = enable != 0;
+  return hip_fail(ctx, e);
+}
+
+int ais_profile_read(ais_ctx* ctx, int which, float* total_ms, int* launches) {
+  if (ctx == nullptr || total_ms == nullptr || launches == nullptr) return AIS_ERR_NULL;
+  if (which < 0 || which >= AIS_K_COUNT_) return AIS_ERR_SIZE;
+  DeviceGuard guard(ctx->device);
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  float total = 0.f;
+  int n = 0;
+  for (auto& t : ctx->timed) {
+    if (t.which != which) continue;
+    float ms = 0.f;
+    e = hipEventElapsedTime(&ms, t.start, t.stop);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    total += ms;
+    ++n;
+  }
+  *total_ms = total;
+  *launches = n;
+  return AIS_OK;
+}
+
+int ais_copy(ais_ctx* ctx, void* dst, const void* src, long long bytes) {
+  if (bytes < 0 || bytes % 16 != 0) return AIS_ERR_SIZE;
+  if (bytes > 0 && (dst == nullptr || src == nullptr)) return AIS_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(dst) % 16 != 0 || reinterpret_cast<uintptr_t>(src) % 16 != 0) return AIS_ERR_ALIGN;
+  if (ctx == nullptr) return AIS_ERR_NULL;
+  DeviceGuard guard(ctx->device);
+  return launch_copy(ctx, dst, src, bytes);
+}
+
+}  // extern "C"

@@ -1,0 +1,328 @@
+// Per-row scalar work and the batch-wide reductions of the path.
+//
+// The batch is a set of variable-length segments (responses) of rows, some rows masked out.  A small
+// plan kernel cuts every response into tiles of kTileRows rows; level 1 reduces one tile per workgroup
+// through LDS to a partial; level 2 (one workgroup) folds the partials of each response in order, forms
+// the group-relative advantages (Eq. 3) and the batch moments, and evaluates the three diagnostics and
+// the mixing coefficient (Eq. 12-17).  Everything is accumulated in fp64 in a fixed order (no floating
+// point atomics), so results are bit-reproducible from run to run.  These kernels move a few bytes per
+// row (about a megabyte per batch) and are latency-bound; the time of the path is in the two sweeps.
+#include "ais_internal.h"
+
+namespace ais {
+namespace {
+
+__device__ __forceinline__ long long clampll(long long v, long long lo, long long hi) {
+  return v < lo ? lo : (v > hi ? hi : v);
+}
+
+// Row range of response i, forced into [0, n_rows] and non-negative length whatever cu_rows holds.
+__device__ __forceinline__ void response_rows(const long long* cu_rows, int i, long long n_rows, long long& lo,
+                                              long long& hi) {
+  lo = clampll(cu_rows[i], 0, n_rows);
+  hi = clampll(cu_rows[i + 1], lo, n_rows);
+}
+
+// ---- plan: tile_off[i] = first tile of response i, tile_off[n_resp] = number of tiles -------------------
+// One workgroup.  Each thread owns a contiguous chunk of responses; thread 0 scans the 256 chunk totals.
+__global__ __launch_bounds__(kTileThreads) void plan_kernel(const long long* __restrict__ cu_rows, int n_resp,
+                                                            long long n_rows, int* __restrict__ tile_off,
+                                                            int max_tiles, int* __restrict__ status) {
+  __shared__ long long chunk_sum[kTileThreads];
+  const int tid = threadIdx.x;
+  const int per = (n_resp + kTileThreads - 1) / kTileThreads;
+  const int i0 = min(n_resp, tid * per), i1 = min(n_resp, i0 + per);
+  long long sum = 0;
+  bool bad = false;
+  for (int i = i0; i < i1; ++i) {
+    long long lo, hi;
+    response_rows(cu_rows, i, n_rows, lo, hi);
+    bad |= (cu_rows[i] != lo) || (cu_rows[i + 1] != hi);
+    sum += (hi - lo + kTileRows - 1) / kTileRows;
+  }
+  if (tid == 0 && n_resp > 0) bad |= (cu_rows[0] != 0) || (cu_rows[n_resp] != n_rows);
+  chunk_sum[tid] = sum;
+  __syncthreads();
+  if (tid == 0) {
+    long long run = 0;
+    for (int t = 0; t < kTileThreads; ++t) {
+      long long s = chunk_sum[t];
+      chunk_sum[t] = run;
+      run += s;
+    }
+    if (run > max_tiles) bad = true;             // cannot happen when cu_rows is a partition of the rows
+    tile_off[n_resp] = (int)clampll(run, 0, max_tiles);
+  }
+  __syncthreads();
+  long long run = chunk_sum[tid];
+  for (int i = i0; i < i1; ++i) {
+    long long lo, hi;
+    response_rows(cu_rows, i, n_rows, lo, hi);
+    tile_off[i] = (int)clampll(run, 0, max_tiles);
+    run += (hi - lo + kTileRows - 1) / kTileRows;
+  }
+  if (bad) atomicOr(status, AIS_STATUS_BAD_CU);
+}
+
+// Response that owns tile b: the last i with tile_off[i] <= b.
+__device__ __forceinline__ int find_response(const int* __restrict__ tile_off, int n_resp, int b) {
+  int lo = 0, hi = n_resp;          // invariant: tile_off[lo] <= b < tile_off[hi]
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (tile_off[mid] <= b) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// Workgroup-wide sum through LDS in a fixed tree order; result valid in thread 0.
+template <typename V>
+__device__ __forceinline__ V block_sum(V v, V* lds) {
+  const int tid = threadIdx.x;
+  lds[tid] = v;
+  __syncthreads();
+#pragma unroll
+  for (int s = kTileThreads / 2; s > 0; s >>= 1) {
+    if (tid < s) lds[tid] += lds[tid + s];
+    __syncthreads();
+  }
+  V r = lds[0];
+  __syncthreads();
+  return r;
+}
+
+// ---- level 1: one tile of one response -> DiagPartial -----------------------------------------------------
+__global__ __launch_bounds__(kTileThreads) void diag_partial_kernel(
+    const float* __restrict__ logp_train, const float* __restrict__ logp_roll,
+    const unsigned char* __restrict__ valid, long long n_rows, const long long* __restrict__ cu_rows, int n_resp,
+    const int* __restrict__ tile_off, float C, DiagPartial* __restrict__ partial) {
+  __shared__ double lds_d[kTileThreads];
+  __shared__ long long lds_i[kTileThreads];
+  const int b = blockIdx.x;
+  if (b >= tile_off[n_resp]) return;                 // uniform for the workgroup
+  const int i = find_response(tile_off, n_resp, b);
+  long long lo, hi;
+  response_rows(cu_rows, i, n_rows, lo, hi);
+  const long long r0 = lo + (long long)(b - tile_off[i]) * kTileRows;
+  const long long r1 = min(hi, r0 + kTileRows);
+  const double lnC = log((double)C);
+  double su = 0, su2 = 0, sabs = 0;
+  long long cnt = 0, nclip = 0;
+  for (long long n = r0 + threadIdx.x; n < r1; n += kTileThreads) {
+    if (valid != nullptr && valid[n] == 0) continue;
+    const double d = (double)logp_train[n] - (double)logp_roll[n];      // log rho (Alg. 1, sampler-trainer ratio)
+    const double u = exp(fmin(d, lnC)) - 1.0;                            // w_bar - 1, w_bar = min(rho, C) (Eq. 10)
+    su += u;
+    su2 += u * u;
+    sabs += fabs(d);
+    cnt += 1;
+    nclip += (d > lnC) ? 1 : 0;
+  }
+  DiagPartial p;
+  p.su = block_sum(su, lds_d);
+  p.su2 = block_sum(su2, lds_d);
+  p.sabs = block_sum(sabs, lds_d);
+  p.cnt = block_sum(cnt, lds_i);
+  p.nclip = block_sum(nclip, lds_i);
+  if (threadIdx.x == 0) partial[b] = p;
+}
+
+// ---- level 2: responses -> advantages, batch moments, diagnostics, alpha --------------------------------------
+__global__ __launch_bounds__(kTileThreads) void diag_final_kernel(
+    const DiagPartial* __restrict__ partial, const int* __restrict__ tile_off, int n_resp, int group_size,
+    const float* __restrict__ rewards, ais_params p, float* __restrict__ adv_out, int* __restrict__ count_out,
+    ais_diag* __restrict__ diag_out, const int* __restrict__ status) {
+  __shared__ double lds_d[kTileThreads];
+  __shared__ long long lds_i[kTileThreads];
+  double su = 0, su2 = 0, sabs = 0, sa = 0, sa2 = 0, saw = 0, saw2 = 0;
+  long long cnt = 0, nclip = 0;
+  for (int i = threadIdx.x; i < n_resp; i += kTileThreads) {
+    // fold this response's tiles in order
+    double r_su = 0, r_su2 = 0, r_sabs = 0;
+    long long r_cnt = 0, r_nclip = 0;
+    for (int t = tile_off[i]; t < tile_off[i + 1]; ++t) {
+      r_su += partial[t].su;
+      r_su2 += partial[t].su2;
+      r_sabs += partial[t].sabs;
+      r_cnt += partial[t].cnt;
+      r_nclip += partial[t].nclip;
+    }
+    // group-relative advantage (Eq. 3): reward minus the mean over the G responses of the prompt
+    const int g0 = (i / group_size) * group_size;
+    double mean = 0;
+    for (int j = 0; j < group_size; ++j) mean += (double)rewards[g0 + j];
+    mean /= group_size;
+    double a = (double)rewards[i] - mean;
+    if (p.adv_mode == 1) {
+      double var = 0;
+      for (int j = 0; j < group_size; ++j) {
+        const double e = (double)rewards[g0 + j] - mean;
+        var += e * e;
+      }
+      a /= sqrt(var / group_size) + (double)p.eps_std;
+    }
+    const float a32 = (float)a;
+    adv_out[i] = a32;
+    count_out[i] = (int)r_cnt;
+    a = (double)a32;                     // the advantage every later step sees is the stored fp32 value
+    // token-level moments of A and A w_bar: A is constant over the response's rows
+    const double sw = r_su + (double)r_cnt;                       // sum w_bar
+    const double sw2 = r_su2 + 2.0 * r_su + (double)r_cnt;        // sum w_bar^2
+    su += r_su; su2 += r_su2; sabs += r_sabs; cnt += r_cnt; nclip += r_nclip;
+    sa += a * (double)r_cnt;
+    sa2 += a * a * (double)r_cnt;
+    saw += a * sw;
+    saw2 += a * a * sw2;
+  }
+  su = block_sum(su, lds_d);
+  su2 = block_sum(su2, lds_d);
+  sabs = block_sum(sabs, lds_d);
+  sa = block_sum(sa, lds_d);
+  sa2 = block_sum(sa2, lds_d);
+  saw = block_sum(saw, lds_d);
+  saw2 = block_sum(saw2, lds_d);
+  cnt = block_sum(cnt, lds_i);
+  nclip = block_sum(nclip, lds_i);
+  if (threadIdx.x != 0) return;
+
+  ais_diag d;
+  d.n_valid = cnt;
+  d.status = *status;
+  d.reserved = 0;
+  if (cnt == 0) {
+    d.mean_w = d.var_w = d.cv2 = d.dbar = d.std_a = d.std_aw = d.dsigma = 0.0;
+    d.ess_ratio = 1.0; d.alpha_ess = 1.0; d.alpha_mis = 0.0; d.alpha_var = 0.0; d.clip_frac = 0.0;
+    d.alpha = 0.0;
+  } else {
+    const double N = (double)cnt;
+    const double mu_u = su / N;
+    d.mean_w = 1.0 + mu_u;
+    d.var_w = fmax(0.0, su2 / N - mu_u * mu_u);               // variance is shift-invariant: var(w_bar) = var(u)
+    d.cv2 = d.var_w / (d.mean_w * d.mean_w);
+    d.ess_ratio = 1.0 / (1.0 + d.cv2);
+    d.alpha_ess = 1.0 / sqrt(1.0 + d.cv2);                    // Eq. 12
+    d.dbar = sabs / N;                                        // Eq. 13
+    d.alpha_mis = fmin(1.0, d.dbar / (double)p.delta);        // Eq. 14
+    const double ma = sa / N, maw = saw / N;
+    d.std_a = sqrt(fmax(0.0, sa2 / N - ma * ma));
+    d.std_aw = sqrt(fmax(0.0, saw2 / N - maw * maw));
+    d.dsigma = d.std_aw / (d.std_a + (double)p.eps_std);      // Eq. 15
+    d.alpha_var = fmax(0.0, (d.dsigma - (double)p.gamma) / (double)p.gamma);   // Eq. 16
+    const double rel = fmin(1.0, fmax(0.0, d.alpha_ess - (double)p.beta_var * d.alpha_var));
+    d.alpha = rel * d.alpha_mis;                              // Eq. 17
+    d.clip_frac = (double)nclip / N;
+  }
+  if (p.alpha_override >= 0.f) d.alpha = (double)p.alpha_override;
+  *diag_out = d;
+}
+
+// ---- per-row coefficient of the gradient, rectification weight, loss partials -------------------------------------
+__global__ __launch_bounds__(kTileThreads) void row_coeff_kernel(
+    const float* __restrict__ logp_train, const float* __restrict__ logp_roll, const float* __restrict__ logp_old,
+    const float* __restrict__ logp_ref, const unsigned char* __restrict__ valid, long long n_rows,
+    const long long* __restrict__ cu_rows, int n_resp, const float* __restrict__ adv,
+    const int* __restrict__ count, const ais_diag* __restrict__ diag, ais_params p,
+    const int* __restrict__ tile_off, double* __restrict__ partial, float* __restrict__ g_out,
+    float* __restrict__ wtilde_out) {
+  __shared__ double lds_d[kTileThreads];
+  const int b = blockIdx.x;
+  if (b >= tile_off[n_resp]) return;
+  const int i = find_response(tile_off, n_resp, b);
+  long long lo, hi;
+  response_rows(cu_rows, i, n_rows, lo, hi);
+  const long long r0 = lo + (long long)(b - tile_off[i]) * kTileRows;
+  const long long r1 = min(hi, r0 + kTileRows);
+  const double alpha = diag->alpha;
+  const double a = (double)adv[i];
+  const int cnt = count[i];
+  const double wgt = cnt > 0 ? 1.0 / ((double)n_resp * (double)cnt) : 0.0;   // 1/G and 1/|o_i| of Eq. 19 over all prompts
+  const double lnC = log((double)p.C);
+  const double lo_clip = 1.0 - (double)p.clip_eps, hi_clip = 1.0 + (double)p.clip_eps;
+  const bool kl = (logp_ref != nullptr) && (p.beta_kl > 0.f);
+  double acc = 0;
+  for (long long n = r0 + threadIdx.x; n < r1; n += kTileThreads) {
+    float g = 0.f, wt = 0.f;
+    if (valid == nullptr || valid[n] != 0) {
+      const double lt = (double)logp_train[n];
+      const double wbar = exp(fmin(lt - (double)logp_roll[n], lnC));
+      const double wtilde = 1.0 + alpha * (wbar - 1.0);                       // Eq. 18 / Alg. 1 rectification weight
+      const double rho_on = logp_old != nullptr ? exp(lt - (double)logp_old[n]) : 1.0;
+      const double clipped = fmin(fmax(rho_on, lo_clip), hi_clip);
+      // the unclipped branch is the minimum (ties included) iff the ratio has not left the trust
+      // region on the side the advantage pushes towards
+      const bool active = (a >= 0.0) ? (rho_on <= hi_clip) : (rho_on >= lo_clip);
+      const double s = active ? rho_on * a : clipped * a;
+      double obj = wtilde * s;
+      double dobj = active ? wtilde * a * rho_on : 0.0;
+      if (kl) {
+        const double q = (double)logp_ref[n] - lt;
+        const double eq = exp(q);
+        obj -= (double)p.beta_kl * (eq - q - 1.0);
+        dobj -= (double)p.beta_kl * (1.0 - eq);
+      }
+      acc -= wgt * obj;
+      g = (float)(wgt * dobj);
+      wt = (float)wtilde;
+    }
+    g_out[n] = g;
+    if (wtilde_out != nullptr) wtilde_out[n] = wt;
+  }
+  acc = block_sum(acc, lds_d);
+  if (threadIdx.x == 0) partial[b] = acc;
+}
+
+__global__ __launch_bounds__(kTileThreads) void loss_final_kernel(const double* __restrict__ partial,
+                                                                  const int* __restrict__ tile_off, int n_resp,
+                                                                  double* __restrict__ loss_out) {
+  __shared__ double lds_d[kTileThreads];
+  const int n_tiles = tile_off[n_resp];
+  double acc = 0;
+  for (int t = threadIdx.x; t < n_tiles; t += kTileThreads) acc += partial[t];
+  acc = block_sum(acc, lds_d);
+  if (threadIdx.x == 0) *loss_out = acc;
+}
+
+}  // namespace
+
+WorkspaceLayout workspace_layout(long long n_rows, int n_resp) {
+  auto up = [](size_t v) { return (v + 255) & ~size_t(255); };
+  WorkspaceLayout w;
+  w.max_tiles = (int)((n_rows + kTileRows - 1) / kTileRows) + n_resp;
+  w.tile_off = 0;
+  w.partial = up(w.tile_off + sizeof(int) * (size_t)(n_resp + 1));
+  w.g = up(w.partial + sizeof(DiagPartial) * (size_t)w.max_tiles);
+  w.total = up(w.g + sizeof(float) * (size_t)n_rows);
+  return w;
+}
+
+int launch_plan(ais_ctx* ctx, const long long* cu_rows, int n_resp, long long n_rows, int* tile_off,
+                int max_tiles) {
+  plan_kernel<<<1, kTileThreads, 0, ctx->stream>>>(cu_rows, n_resp, n_rows, tile_off, max_tiles, ctx->status_dev);
+  return hip_fail(ctx, hipGetLastError());
+}
+
+int launch_diagnostics(ais_ctx* ctx, const float* logp_train, const float* logp_roll, const unsigned char* valid,
+                       long long n_rows, const long long* cu_rows, int n_resp, int group_size,
+                       const float* rewards, const ais_params& p, const int* tile_off, int max_tiles,
+                       DiagPartial* partial, float* adv_out, int* count_out, ais_diag* diag_out) {
+  if (max_tiles > 0)
+    diag_partial_kernel<<<max_tiles, kTileThreads, 0, ctx->stream>>>(logp_train, logp_roll, valid, n_rows, cu_rows,
+                                                                     n_resp, tile_off, p.C, partial);
+  diag_final_kernel<<<1, kTileThreads, 0, ctx->stream>>>(partial, tile_off, n_resp, group_size, rewards, p, adv_out,
+                                                         count_out, diag_out, ctx->status_dev);
+  return hip_fail(ctx, hipGetLastError());
+}
+
+int launch_row_coeff(ais_ctx* ctx, const float* logp_train, const float* logp_roll, const float* logp_old,
+                     const float* logp_ref, const unsigned char* valid, long long n_rows,
+                     const long long* cu_rows, int n_resp, const float* adv, const int* count,
+                     const ais_diag* diag, const ais_params& p, const int* tile_off, int max_tiles,
+                     double* partial, float* g_out, float* wtilde_out, double* loss_out) {
+  if (max_tiles > 0)
+    row_coeff_kernel<<<max_tiles, kTileThreads, 0, ctx->stream>>>(logp_train, logp_roll, logp_old, logp_ref, valid,
+                                                                  n_rows, cu_rows, n_resp, adv, count, diag, p,
+                                                                  tile_off, partial, g_out, wtilde_out);
+  loss_final_kernel<<<1, kTileThreads, 0, ctx->stream>>>(partial, tile_off, n_resp, loss_out);
+  return hip_fail(ctx, hipGetLastError());
+}
+
+}  // namespace ais

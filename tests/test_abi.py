@@ -1,0 +1,128 @@
+"""The C ABI without a GPU: the library loads, exports every function include/ais.h declares, fills in
+the paper's defaults, and rejects bad arguments on the host before touching any device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2605_13907_amd import binding as B
+from tests.test_golden import read_golden
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = open(os.path.join(ROOT, "include", "ais.h")).read()
+
+
+def declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", HEADER, flags=re.S)
+    names = re.findall(r"^\s*(?:const\s+)?(?:int|void|char\s*\*)\s*\*?\s*(ais_\w+)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = C.CDLL(B.LIB_PATH)
+    names = declared_functions()
+    assert {"ais_token_logprob", "ais_diagnostics", "ais_grpo_loss_grad", "ais_create", "ais_destroy"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(B.SYMBOLS), "binding and header disagree on the set of functions"
+
+
+def test_struct_sizes_match_header_layout():
+    assert C.sizeof(B.AisParams) == 40          # 9 floats + 1 int
+    assert C.sizeof(B.AisDiag) == 8 + 13 * 8 + 8
+
+
+def test_defaults_are_the_papers():
+    g = read_golden("hyperparameters.txt")
+    p = B.default_params()
+    for k in ("C", "delta", "gamma", "eps_std", "clip_eps"):
+        assert getattr(p, k) == pytest.approx(g[k], rel=1e-7), k
+    assert p.adv_mode == 0 and p.alpha_override < 0 and p.inv_temperature == 1.0 and p.beta_kl == 0.0
+    assert p.beta_var == 1.0
+
+
+def test_strerror_and_version():
+    lib = B._lib()
+    assert lib.ais_version() >= 1000
+    for code in range(0, -10, -1):
+        assert len(lib.ais_strerror(code)) > 0
+    assert lib.ais_strerror(0) == b"ok"
+
+
+FAKE = C.c_void_p(0x1000)       # never dereferenced: validation fails (or ctx is NULL) before any launch
+
+
+def call_logprob(**kw):
+    a = dict(ctx=None, logits=FAKE, dtype=B.AIS_BF16, n_rows=4, vocab=64, stride=64, tok=FAKE, valid=None,
+             inv_t=1.0, logp=FAKE, lse=FAKE)
+    a.update(kw)
+    return B._lib().ais_token_logprob(a["ctx"], a["logits"], a["dtype"], a["n_rows"], a["vocab"], a["stride"],
+                                      a["tok"], a["valid"], a["inv_t"], a["logp"], a["lse"])
+
+
+def test_token_logprob_argument_checks():
+    assert call_logprob() == -1                                  # everything fine except the NULL context
+    assert call_logprob(logits=None) == -1
+    assert call_logprob(tok=None) == -1
+    assert call_logprob(n_rows=-1) == -2
+    assert call_logprob(vocab=0) == -2
+    assert call_logprob(vocab=2 ** 31) == -2
+    assert call_logprob(stride=63) == -3
+    assert call_logprob(dtype=7) == -7
+    assert call_logprob(logits=C.c_void_p(0x1001)) == -4
+    assert call_logprob(inv_t=0.0) == -5
+    assert call_logprob(inv_t=float("nan")) == -5
+    assert call_logprob(n_rows=0, logits=None, tok=None, logp=None, lse=None) == -1   # only the context is missing
+
+
+def call_diag(params=None, **kw):
+    p = params or B.default_params()
+    a = dict(ctx=None, lt=FAKE, lr=FAKE, valid=None, n_rows=10, cu=FAKE, n_resp=8, G=4, rewards=FAKE,
+             adv=FAKE, count=FAKE, diag=FAKE)
+    a.update(kw)
+    return B._lib().ais_diagnostics(a["ctx"], a["lt"], a["lr"], a["valid"], a["n_rows"], a["cu"], a["n_resp"],
+                                    a["G"], a["rewards"], C.byref(p), a["adv"], a["count"], a["diag"])
+
+
+def test_diagnostics_argument_checks():
+    assert call_diag() == -1
+    assert call_diag(n_resp=0) == -2
+    assert call_diag(G=0) == -2
+    assert call_diag(n_resp=9) == -6
+    assert call_diag(cu=None) == -1
+    assert call_diag(diag=None) == -1
+    for bad in (dict(C=0.5), dict(delta=0.0), dict(gamma=-1.0), dict(eps_std=-1e-3), dict(alpha_override=1.5),
+                dict(adv_mode=2), dict(clip_eps=1.0), dict(inv_temperature=0.0), dict(beta_kl=-1.0),
+                dict(beta_var=float("nan"))):
+        assert call_diag(params=B.default_params(**bad)) == -5, bad
+
+
+def test_loss_grad_argument_checks():
+    lib = B._lib()
+    p = B.default_params()
+
+    def call(**kw):
+        a = dict(ctx=None, logits=FAKE, dtype=B.AIS_BF16, n_rows=4, vocab=64, stride=64, tok=FAKE, valid=None,
+                 cu=FAKE, n_resp=2, lt=FAKE, lse=FAKE, lr=FAKE, lo=None, lref=None, adv=FAKE, count=FAKE,
+                 diag=FAKE, wt=None, loss=FAKE, dz=FAKE)
+        a.update(kw)
+        return lib.ais_grpo_loss_grad(a["ctx"], a["logits"], a["dtype"], a["n_rows"], a["vocab"], a["stride"],
+                                      a["tok"], a["valid"], a["cu"], a["n_resp"], a["lt"], a["lse"], a["lr"],
+                                      a["lo"], a["lref"], a["adv"], a["count"], a["diag"], C.byref(p), a["wt"],
+                                      a["loss"], a["dz"])
+
+    assert call() == -1
+    assert call(dz=None) == -1
+    assert call(loss=None) == -1
+    assert call(stride=8) == -3
+    assert call(n_resp=0) == -2
+    assert call(dz=C.c_void_p(0x2001)) == -4
+    assert call(dtype=3) == -7
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_LIB", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError):
+        B._lib()

@@ -1,0 +1,262 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU fp64 oracle on the same seeded inputs.
+Tolerances are defined in tests/parity.py."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_13907_amd import binding as B
+from paper_2605_13907_amd import workloads as W
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = B.AisContext()
+    yield c
+    c.close()
+
+
+def gen(shape, **kw):
+    return W.generate(shape, "cuda", **kw)
+
+
+# ------------------------------------------------------------------ the five workloads, at oracle-sized scale
+def test_config1_tiny_full_size(ctx):
+    """Workload 1 as specified: fp32 logits, padded layout, V = 1024."""
+    batch = gen(W.config(1))
+    assert batch.logits.dtype == torch.float32 and batch.n_rows == 8 * 64
+    out, ref, d = P.check(ctx, batch)
+    assert 0 < d["n_valid"] < batch.n_rows
+
+
+@pytest.mark.parametrize("k,len_div", [(2, 64), (3, 16), (4, 64), (5, 128)])
+def test_configs_full_vocab_fewer_rows(ctx, k, len_div):
+    """Workloads 2-5 at their real vocabulary (the kernels' real row geometry, many unrolled iterations plus
+    the ragged tail), with response lengths divided so that the oracle finishes in seconds."""
+    n_prompts = 2 if k == 3 else None
+    shape = W.config(k).scaled(len_div=len_div, n_prompts=n_prompts)
+    batch = gen(shape, row_chunk=128)
+    out, ref, d = P.check(ctx, batch)
+    assert d["n_valid"] > 100
+    if k == 5:      # extra rollout noise: mismatch far above delta, correction fully engaged on the necessity side
+        assert d["alpha_mis"] == 1.0
+
+
+@pytest.mark.parametrize("k,vocab,len_div", [(2, 20_008, 8), (3, 4_104, 2), (4, 33_000, 8), (5, 8_200, 16)])
+def test_configs_many_rows_smaller_vocab(ctx, k, vocab, len_div):
+    """The same structures with more rows (several reduction tiles per response, more responses than one tile row)."""
+    shape = W.config(k).scaled(vocab=vocab, len_div=len_div)
+    batch = gen(shape)
+    out, ref, d = P.check(ctx, batch)
+    assert batch.n_rows > 2000
+
+
+# ------------------------------------------------------------------ adversarial shapes
+@pytest.mark.parametrize("vocab", [1, 5, 255, 1003, 2056, 8191])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_odd_vocabularies(ctx, vocab, dtype):
+    """Vocabularies below one workgroup, not a multiple of the vector width, or with a row pitch that is not
+    16-byte aligned (element-wise path)."""
+    shape = W.RolloutShape("odd", n_prompts=2, group_size=4, vocab=vocab, logits_dtype=dtype, sigma=2.5, boost=4.0,
+                           layout="padded", max_len=12, length_dist=("uniform", 1, 12), reward_p=0.5, seed=vocab)
+    batch = gen(shape)
+    batch.rewards[:] = torch.tensor([1, 0, 0, 1, 0, 0, 1, 0], dtype=torch.float32)
+    P.check(ctx, batch)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_padded_pitch_and_misaligned_base(ctx, dtype):
+    """row_stride > vocab (a column slice of a wider matrix): vector body plus scalar tail; and a base pointer
+    that is not 16-byte aligned: element-wise path."""
+    shape = W.RolloutShape("pitch", n_prompts=1, group_size=4, vocab=3003, logits_dtype=dtype, sigma=3.0, boost=0.0,
+                           layout="packed", max_len=40, length_dist=("uniform", 5, 40), reward_p=0.5, seed=77)
+    batch = gen(shape)
+    batch.rewards[:] = torch.tensor([1, 0, 0, 1], dtype=torch.float32)
+    R, V = batch.logits.shape
+    wide = torch.full((R, 3008 + 8), 8192.0, dtype=batch.logits.dtype, device="cuda")    # poison outside the row
+    wide[:, :V] = batch.logits
+    batch.logits = wide[:, :V]
+    assert batch.logits.stride(0) == 3016
+    out, _, _ = P.check(ctx, batch)
+    assert bool((wide[:, V:] == 8192.0).all()), "columns beyond vocab must not be touched"
+    # misaligned base: shift by one element
+    flat = torch.empty(R * V + 1, dtype=batch.logits.dtype, device="cuda")
+    flat[1:] = batch.logits.reshape(-1)
+    batch.logits = flat[1:].view(R, V)
+    assert batch.logits.data_ptr() % 16 != 0
+    P.check(ctx, batch)
+
+
+def test_degenerate_batches(ctx):
+    shape = W.RolloutShape("deg", n_prompts=2, group_size=4, vocab=520, logits_dtype="bf16", sigma=3.0, boost=0.0,
+                           layout="padded", max_len=16, length_dist=("uniform", 1, 16), reward_p=0.5, seed=5)
+    # a response with no valid row, and a prompt whose rewards are all equal
+    batch = gen(shape)
+    batch.valid.view(8, 16)[2] = 0
+    batch.token_ids.view(8, 16)[2] = -1
+    batch.rewards[:] = torch.tensor([1, 0, 1, 1, 1, 1, 1, 1], dtype=torch.float32)
+    out, ref, d = P.check(ctx, batch)
+    assert out["count"][2].item() == 0
+    # all rewards equal everywhere: advantages 0, loss 0, gradient identically 0
+    batch.rewards[:] = 1.0
+    out, ref, d = P.check(ctx, batch)
+    assert float(out["loss"].item()) == 0.0 and not bool(out["dlogits"].any())
+    assert d["alpha_var"] == 0.0 and d["dsigma"] == 0.0
+    # nothing valid at all
+    batch.valid[:] = 0
+    batch.token_ids[:] = -1
+    batch.rewards[:] = torch.tensor([1, 0, 1, 1, 0, 0, 1, 0], dtype=torch.float32)
+    out, ref, d = P.check(ctx, batch)
+    assert d["n_valid"] == 0 and d["alpha"] == 0.0 and not bool(out["dlogits"].any())
+
+
+def test_single_row_and_empty(ctx):
+    shape = W.RolloutShape("one", n_prompts=1, group_size=1, vocab=777, logits_dtype="bf16", sigma=3.0, boost=0.0,
+                           layout="packed", max_len=1, length_dist=("uniform", 1, 1), reward_p=1.0, seed=9)
+    batch = gen(shape)
+    P.check(ctx, batch)              # one response alone in its group: advantage 0
+    # zero rows: every call must accept it and launch nothing harmful
+    z = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    tok = torch.empty(0, dtype=torch.int32, device="cuda")
+    logp, lse = ctx.token_logprob(z, tok)
+    cu = torch.zeros(3, dtype=torch.int64, device="cuda")
+    rewards = torch.tensor([1.0, 0.0], device="cuda")
+    adv, count, diag = ctx.diagnostics(logp, logp, None, cu, rewards, 2)
+    loss, wt, dz = ctx.grpo_loss_grad(z, tok, None, cu, logp, lse, logp, adv, count, diag)
+    torch.cuda.synchronize()
+    assert ctx.read_diag(diag)["n_valid"] == 0 and float(loss.item()) == 0.0
+    assert adv.tolist() == [0.5, -0.5] and count.tolist() == [0, 0]
+
+
+def test_all_ratios_truncated(ctx):
+    """rho > C on every token: w_bar == C, CV = 0, alpha_ess = 1, clip_frac = 1."""
+    shape = W.config(2).scaled(vocab=1032, len_div=64, seed=21)
+    batch = gen(shape)
+    batch.logp_roll -= 5.0
+    out, ref, d = P.check(ctx, batch)
+    assert d["clip_frac"] == 1.0 and abs(d["mean_w"] - 5.0) < 1e-12 and d["alpha_ess"] == 1.0
+
+
+# ------------------------------------------------------------------ modes of the objective
+@pytest.mark.parametrize("mode", ["grpo", "tis", "alpha_0.37", "adv_norm", "temperature", "beta_var", "C2"])
+def test_modes(ctx, mode):
+    shape = W.config(5).scaled(vocab=2600, len_div=256, seed=31)
+    batch = gen(shape)
+    kw = {"grpo": dict(alpha_override=0.0), "tis": dict(alpha_override=1.0), "alpha_0.37": dict(alpha_override=0.37),
+          "adv_norm": dict(adv_mode=1), "temperature": dict(inv_temperature=1 / 0.9), "beta_var": dict(beta_var=0.25),
+          "C2": dict(C=2.0)}[mode]
+    out, ref, d = P.check(ctx, batch, B.default_params(**kw))
+    if mode == "grpo":
+        assert bool((out["wtilde"][batch.valid.bool()] == 1).all())
+
+
+@pytest.mark.parametrize("with_kl", [False, True])
+def test_stale_old_policy_and_kl(ctx, with_kl):
+    """log pi_old != log pi_train: ratios on both sides of the clip range; optionally the KL term."""
+    shape = W.config(4).scaled(vocab=3000, len_div=32, seed=41)
+    batch = gen(shape)
+    # inputs of the method must not come from the path under test: torch's own log_softmax stands in for the
+    # trainer's log-probs when building the stale old-policy and reference log-probs
+    logp = torch.log_softmax(batch.logits.float(), dim=1).gather(1, batch.token_ids.long().unsqueeze(1)).squeeze(1)
+    g = torch.Generator(device="cuda").manual_seed(3)
+    logp_old = logp + 0.25 * torch.randn(logp.shape, device="cuda", generator=g)
+    # keep ratios away from the clip edges so that fp32 vs fp64 log-probs cannot flip a branch
+    rho = torch.exp(logp - logp_old)
+    near = ((rho - 0.8).abs() < 1e-3) | ((rho - 1.2).abs() < 1e-3)
+    logp_old = torch.where(near, logp, logp_old)
+    p = B.default_params(beta_kl=0.04 if with_kl else 0.0)
+    logp_ref = logp + 0.3 * torch.randn(logp.shape, device="cuda", generator=g) if with_kl else None
+    out, ref, d = P.check(ctx, batch, p, logp_old=logp_old, logp_ref=logp_ref)
+    rho = np.exp(ref["logp"] - P.to_np64(logp_old))
+    assert (rho > 1.2).any() and (rho < 0.8).any()
+
+
+def test_in_place_gradient(ctx):
+    shape = W.config(2).scaled(vocab=4104, len_div=32, seed=51)
+    batch = gen(shape)
+    ptr = batch.logits.data_ptr()
+    out, ref, d = P.check(ctx, batch, in_place=True)
+    assert out["dlogits"].data_ptr() == ptr
+
+
+# ------------------------------------------------------------------ reproducibility and device-detected faults
+def test_bit_reproducible(ctx):
+    shape = W.config(3).scaled(vocab=5000, len_div=4, n_prompts=2, seed=61)
+    batch = gen(shape)
+    a = ctx.step(batch)
+    b = ctx.step(batch)
+    torch.cuda.synchronize()
+    for k in ("logp", "lse", "adv", "count", "diag", "loss", "wtilde", "dlogits"):
+        assert torch.equal(a[k], b[k]), k
+
+
+def test_bad_token_is_flagged_not_dereferenced(ctx):
+    shape = W.config(2).scaled(vocab=1000, len_div=128, seed=71)
+    batch = gen(shape)
+    batch.token_ids[3] = 1000          # == vocab
+    batch.token_ids[7] = -5
+    batch.token_ids[9] = 2 ** 30
+    out = ctx.step(batch)
+    torch.cuda.synchronize()
+    assert ctx.status() & B.STATUS_BAD_TOKEN
+    assert out["logp"][3].item() == 0 and out["logp"][7].item() == 0 and out["logp"][9].item() == 0
+    assert torch.isfinite(out["dlogits"].float()).all()
+    assert ctx.status() == 0           # reading cleared it
+
+
+def test_bad_cu_rows_is_flagged(ctx):
+    shape = W.config(2).scaled(vocab=512, len_div=128, seed=81)
+    batch = gen(shape)
+    cu = batch.cu_rows.clone()
+    cu[3], cu[4] = cu[4].item(), cu[3].item()          # not monotone
+    cu[-1] = batch.n_rows + 1000                        # beyond the rows
+    logp, lse = ctx.token_logprob(batch.logits, batch.token_ids, batch.valid)
+    adv, count, diag = ctx.diagnostics(logp, batch.logp_roll, batch.valid, cu, batch.rewards, 8)
+    torch.cuda.synchronize()
+    assert ctx.status() & B.STATUS_BAD_CU
+    assert int(count.max().item()) <= batch.n_rows and int(count.min().item()) >= 0   # ranges were clamped
+
+
+def test_full_size_qwen3_8b_sampled(ctx):
+    """Workload 2 at full size, in the launch configuration the benchmark times.  The oracle cannot redo
+    5.6e9 exponentials inside a test, so: log-probs of sampled rows are compared one by one; counts are exact;
+    and every sampled gradient row is checked for the structure the method fixes: it is one scalar times
+    (softmax - onehot) of the oracle's softmax, the scalar has the sign of the response's advantage and its
+    size respects Prop. 2's bound on the mixed weight."""
+    batch = gen(W.config(2), row_chunk=512)
+    out = ctx.step(batch)
+    torch.cuda.synchronize()
+    assert ctx.status() == 0
+    d = ctx.read_diag(out["diag"])
+    R, V = batch.logits.shape
+    assert d["n_valid"] == R and out["count"].cpu().tolist() == batch.lengths.tolist()
+    assert 0.0 <= d["alpha"] <= 1.0 and 0.0 < d["alpha_ess"] <= 1.0
+    rng = np.random.default_rng(0)
+    cu = batch.cu_rows.cpu().numpy()
+    rows = np.unique(np.concatenate([rng.integers(0, R, size=48), cu[:-1], cu[1:] - 1, [0, R - 1]]))
+    idx = torch.from_numpy(rows).cuda()
+    z = P.to_np64(batch.logits[idx])
+    y = batch.token_ids[idx].cpu().numpy()
+    import oracle.ais_oracle as O
+    logp_ref, lse_ref = O.token_logprob(z, y)
+    assert np.abs(P.to_np64(out["logp"][idx]) - logp_ref).max() <= P.LOGP_ATOL
+    assert np.abs(P.to_np64(out["lse"][idx]) - lse_ref).max() <= P.LOGP_ATOL
+    adv = O.group_advantages(P.to_np64(batch.rewards), 8)
+    seq = np.searchsorted(cu, rows, side="right") - 1
+    dz = P.to_np64(out["dlogits"][idx])
+    B_ = batch.shape.n_resp
+    for j, n in enumerate(rows):
+        base = np.exp(z[j] - lse_ref[j])
+        base[y[j]] -= 1.0
+        a = adv[seq[j]]
+        if a == 0:
+            assert not dz[j].any()
+            continue
+        c = float(dz[j] @ base / (base @ base))              # least-squares scalar
+        resid = np.abs(dz[j] - c * base)
+        assert np.all(resid <= P.DZ_REL * np.abs(c * base) + P.DZ_CUSHION * np.abs(c * base).max())
+        wt = c * B_ * batch.lengths[seq[j]].item() / a        # the mixed weight this row was given
+        assert 1 - d["alpha"] - 2e-2 <= wt <= (1 + d["alpha"] * 4.0) * 1.02, wt
+        assert abs(wt - out["wtilde"][n].item()) <= 1e-2 * wt
