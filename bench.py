@@ -21,6 +21,24 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E, vendor figure
 
 
+def measured_traffic(kernel: str, workload: int):
+    """HBM bytes per launch from the hardware-counter summaries under profiles/, or None when there is no
+    summary for this kernel and workload or the kernel source has changed since the counters were taken."""
+    import glob
+    import hashlib
+    import re
+    src = os.path.join(ROOT, "paper_2605_13907_amd", "csrc", "sweeps.hip")
+    sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    for path in glob.glob(os.path.join(ROOT, "profiles", "pmc_hbm_traffic_*.txt")):
+        text = open(path).read()
+        if f"sweeps.hip sha256={sha}" not in text:
+            continue
+        m = re.search(rf"^{kernel} workload={workload} traffic_bytes_per_launch=(\d+)", text, flags=re.M)
+        if m:
+            return int(m.group(1))
+    return None
+
+
 def cpu_baseline(batch, params, sample_rows: int):
     """The CPU oracle, as it stands, on the first `sample_rows` rows of the batch (whole responses are
     not needed: the sample is re-packed as responses of equal length so that every step of the path runs)."""
@@ -139,7 +157,8 @@ def main():
                    "responses": shape.n_resp, "group_size": shape.group_size, "logits": shape.logits_dtype,
                    "layout": shape.layout, "in_place": bool(args.in_place)},
         "roofline": {"bound": "hbm", "kernel": "dlogits_kernel", "achieved": bwd_gbps, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": bwd_gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "unit": "GB/s", "frac": bwd_gbps / HBM_PEAK_GBPS,
+                     "traffic": measured_traffic("dlogits_kernel", args.config),
                      "avg_ms": ms_bwd / n_bwd, "bytes_per_launch": bwd_bytes},
         "kernels": {"token_logprob": {"avg_ms": ms_fwd / n_fwd, "GB/s": fwd_gbps, "frac": fwd_gbps / HBM_PEAK_GBPS},
                     "dlogits": {"avg_ms": ms_bwd / n_bwd, "GB/s": bwd_gbps, "frac": bwd_gbps / HBM_PEAK_GBPS},

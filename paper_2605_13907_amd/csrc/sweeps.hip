@@ -1,7 +1,8 @@
 // The two vocabulary sweeps of the path, and a plain copy kernel used as a bandwidth yardstick.
 //
 //   token_logprob_kernel   one pass over a logits row with a running (max, sum) pair:
-//                          lse = log sum_v exp(z_v / T), logp = z_y / T - lse
+//                          lse = log sum_v exp(z_v / T), logp = z_y / T - lse, the latter evaluated as
+//                          -log1p(sum_{v != y} exp((z_v - z_y) / T))
 //                          (Alg. 1, "Compute full-precision log-probs")
 //   dlogits_kernel         second pass: dz_v = g (softmax_v - 1[v = y]) / T, written in the logits'
 //                          dtype (gradient of Eq. 19 through the log-softmax; g is the row's coefficient)
