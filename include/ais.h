@@ -103,6 +103,9 @@ typedef struct ais_diag {
   double alpha;          /* clip(alpha_ess - beta_var alpha_var, 0, 1) alpha_mis (Eq. 17),
                             or alpha_override                                                  */
   double clip_frac;      /* share of valid rows with rho > C                                   */
+  double kl_roll_train;  /* mean(log pi_roll - log pi_train) over the sampled tokens: the estimate
+                            of KL(pi_roll || pi_train) plotted in Sec. 3.1's training-dynamics figure */
+  double mean_abs_dp;    /* mean |pi_train(x_t) - pi_roll(x_t)|, the E|Delta p| of the same figure   */
   int status;            /* the context's status word at the time of the call                 */
   int reserved;
 } ais_diag;
@@ -187,10 +190,40 @@ int ais_grpo_loss_grad(ais_ctx* ctx, const void* logits, ais_dtype dtype, long l
                        const int* count, const ais_diag* diag, const ais_params* params,
                        float* wtilde_out, double* loss_out, void* dlogits);
 
+/* ---- the rollout-side FP8 perturbation (input generation on the device) ------------------------ */
+
+/* Per-row FP8-E4M3 quantisation of logits: the symmetric scaling of Eq. 1 with the E4M3 value grid
+ * (Sec. 2.1; OCP "fn" format, largest magnitude 448) in place of the integer grid:
+ *   s_n = max_v |z[n, v]| / 448  (1 for an all-zero row),  code[n, v] = e4m3(z[n, v] / s_n)
+ * rounded to nearest, ties to even, saturating; both divisions are correctly rounded fp32.
+ *   codes_out  [n_rows, codes_stride] bytes, the first `vocab` of each row are written
+ *   scale_out  [n_rows] fp32
+ * Errors: as ais_token_logprob, plus codes_stride < vocab (AIS_ERR_STRIDE). */
+int ais_fp8_quantize_rows(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows,
+                          long long vocab, long long row_stride, unsigned char* codes_out,
+                          long long codes_stride, float* scale_out);
+
+/* out[n, v] = s_n * value(code[n, v]) in fp32, stored as `out_dtype` (bf16: rounded to nearest even).
+ * Errors: NULL pointers, sizes, strides < vocab, unknown dtype, misaligned out. */
+int ais_fp8_dequantize_rows(ais_ctx* ctx, const unsigned char* codes, long long codes_stride,
+                            const float* scale, long long n_rows, long long vocab, void* out,
+                            ais_dtype out_dtype, long long out_stride);
+
+/* The rollout policy's log-probability of the sampled tokens under that perturbation:
+ * logp_roll_out[n] = log softmax(z_r[n, :])[y_n] with z_r = dequantise(quantise(z)), computed without
+ * materialising codes or z_r; 0 where valid == 0.  This is what the FP8 sampler would report for the
+ * ratio of Alg. 1 ("Sampler-Trainer ratio").  Errors: as ais_token_logprob. */
+int ais_fp8_rollout_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows,
+                            long long vocab, long long row_stride, const int* token_ids,
+                            const unsigned char* valid, float* logp_roll_out);
+
 /* ---- measurement helpers -------------------------------------------------------------------- */
 
 /* Kernels whose device time can be read back. */
-typedef enum ais_kernel { AIS_K_LOGPROB = 0, AIS_K_DLOGITS = 1, AIS_K_COPY = 2, AIS_K_COUNT_ = 3 } ais_kernel;
+typedef enum ais_kernel {
+  AIS_K_LOGPROB = 0, AIS_K_DLOGITS = 1, AIS_K_COPY = 2, AIS_K_FP8_QUANT = 3, AIS_K_FP8_DEQUANT = 4,
+  AIS_K_FP8_LOGPROB = 5, AIS_K_COUNT_ = 6
+} ais_kernel;
 
 /* With `enable` != 0 every launch of the kernels above is bracketed by HIP events on the
  * context's stream; enabling also clears what was gathered before. */

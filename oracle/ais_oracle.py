@@ -18,7 +18,7 @@ Steps (each function cites the passage it follows):
   O7  gradient of O6 w.r.t. logits  chain rule through log-softmax, alpha / w_tilde / A held constant
                                     (App. "Low-bit Rollout and AIS": signals come from detached tensors)
 
-Readings where the paper is silent (the full list with reasons is in the design notes):
+Readings where the paper is silent:
   * CV and std are population statistics (ddof = 0) over *valid token positions*;
     only ddof = 0 makes the two sides of Eq. 12 equal.
   * alpha is one scalar per batch (Eq. 17 carries no sample index).
@@ -31,9 +31,9 @@ Readings where the paper is silent (the full list with reasons is in the design 
     Parity unpinned by the paper for that term (pinned here only by its own closed forms).
   * temperature: logits are multiplied by inv_temperature before the softmax.
 
-Parity pins for every function are in tests/test_oracle_*.py; numeric values of alpha
+Parity pins for every function are in tests/oracle_pins.py; numeric values of alpha
 for a given input are not printed anywhere in the paper, so they are pinned by closed
-forms derived from Eq. 12-17 (tests/golden/two_point_weights.txt).
+forms worked out by hand from Eq. 12-17 for two-point weight distributions.
 """
 from __future__ import annotations
 
@@ -144,7 +144,8 @@ def diagnostics(logp_train, logp_roll, valid, cu_rows, adv, p: Params):
     out = dict(n_valid=N, count=count)
     if N == 0:
         out.update(mean_w=0.0, var_w=0.0, cv2=0.0, ess_ratio=1.0, dbar=0.0, std_a=0.0, std_aw=0.0,
-                   dsigma=0.0, alpha_ess=1.0, alpha_mis=0.0, alpha_var=0.0, clip_frac=0.0, alpha=0.0)
+                   dsigma=0.0, alpha_ess=1.0, alpha_mis=0.0, alpha_var=0.0, clip_frac=0.0, alpha=0.0,
+                   kl_roll_train=0.0, mean_abs_dp=0.0)
         if p.alpha_override >= 0:
             out["alpha"] = float(p.alpha_override)
         return out
@@ -166,6 +167,11 @@ def diagnostics(logp_train, logp_roll, valid, cu_rows, adv, p: Params):
     out.update(mean_w=mean_w, var_w=var_w, cv2=cv2, ess_ratio=1.0 / (1.0 + cv2), dbar=dbar,
                std_a=std_a, std_aw=std_aw, dsigma=dsigma, alpha_ess=alpha_ess, alpha_mis=alpha_mis,
                alpha_var=alpha_var, clip_frac=float((rho[valid] > p.C).mean()), alpha=alpha)
+    # the two mismatch metrics the paper plots next to the ESS ratio (Sec. 3.1, first paragraph):
+    # KL(pi_roll || pi_train), estimated on the tokens the rollout policy sampled as the mean of
+    # log pi_roll - log pi_train, and the mean absolute probability gap E|Delta p| of those tokens
+    out["kl_roll_train"] = float((-d[valid]).mean())
+    out["mean_abs_dp"] = float(np.abs(np.exp(logp_train[valid]) - np.exp(_f64(logp_roll)[valid])).mean())
     return out
 
 

@@ -17,7 +17,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(PKG, "libais_gfx950.so")
 
 AIS_BF16, AIS_F32 = 0, 1
-AIS_K_LOGPROB, AIS_K_DLOGITS, AIS_K_COPY = 0, 1, 2
+AIS_K_LOGPROB, AIS_K_DLOGITS, AIS_K_COPY, AIS_K_FP8_QUANT, AIS_K_FP8_DEQUANT, AIS_K_FP8_LOGPROB = range(6)
 STATUS_BAD_TOKEN, STATUS_BAD_CU = 1, 2
 
 ERRORS = {
@@ -37,7 +37,7 @@ class AisDiag(C.Structure):
                 ("ess_ratio", C.c_double), ("dbar", C.c_double), ("std_a", C.c_double), ("std_aw", C.c_double),
                 ("dsigma", C.c_double), ("alpha_ess", C.c_double), ("alpha_mis", C.c_double),
                 ("alpha_var", C.c_double), ("alpha", C.c_double), ("clip_frac", C.c_double),
-                ("status", C.c_int), ("reserved", C.c_int)]
+                ("kl_roll_train", C.c_double), ("mean_abs_dp", C.c_double), ("status", C.c_int), ("reserved", C.c_int)]
 
     def as_dict(self):
         return {name: getattr(self, name) for name, _ in self._fields_ if name != "reserved"}
@@ -67,6 +67,9 @@ SYMBOLS = {
     "ais_diagnostics": (_I, [_P, _P, _P, _P, _LL, _P, _I, _I, _P, C.POINTER(AisParams), _P, _P, _P]),
     "ais_grpo_loss_grad": (_I, [_P, _P, _I, _LL, _LL, _LL, _P, _P, _P, _I, _P, _P, _P, _P, _P, _P, _P, _P,
                                 C.POINTER(AisParams), _P, _P, _P]),
+    "ais_fp8_quantize_rows": (_I, [_P, _P, _I, _LL, _LL, _LL, _P, _LL, _P]),
+    "ais_fp8_dequantize_rows": (_I, [_P, _P, _LL, _P, _LL, _LL, _P, _I, _LL]),
+    "ais_fp8_rollout_logprob": (_I, [_P, _P, _I, _LL, _LL, _LL, _P, _P, _P]),
     "ais_profile": (_I, [_P, _I]),
     "ais_profile_read": (_I, [_P, _I, C.POINTER(_F), C.POINTER(_I)]),
     "ais_copy": (_I, [_P, _P, _P, _LL]),
@@ -240,6 +243,45 @@ class AisContext:
                                                batch.logp_roll, adv, count, diag, p, logp_old, logp_ref,
                                                dlogits=batch.logits if in_place else None)
         return dict(logp=logp, lse=lse, adv=adv, count=count, diag=diag, loss=loss, wtilde=wtilde, dlogits=dz)
+
+    # ------------------------------------------------------------------ FP8 rollout perturbation
+    def fp8_quantize_rows(self, logits):
+        """-> (codes [R, V] uint8, scale [R] fp32).  See ais_fp8_quantize_rows in include/ais.h."""
+        n_rows, vocab, row_stride = _logits_geometry(logits)
+        codes = torch.empty((n_rows, vocab), dtype=torch.uint8, device=self.device)
+        scale = torch.empty(n_rows, dtype=torch.float32, device=self.device)
+        self._sync_stream()
+        rc = self._lib.ais_fp8_quantize_rows(self._h, C.c_void_p(logits.data_ptr()), _dtype_code(logits), n_rows,
+                                             vocab, row_stride, _ptr(codes), vocab, _ptr(scale))
+        if rc != 0:
+            raise AisError(rc, "ais_fp8_quantize_rows")
+        return codes, scale
+
+    def fp8_dequantize_rows(self, codes, scale, dtype=torch.float32):
+        """-> z_r [R, V] of `dtype` (float32 or bfloat16)."""
+        n_rows, vocab = codes.shape
+        out = torch.empty((n_rows, vocab), dtype=dtype, device=self.device)
+        self._sync_stream()
+        rc = self._lib.ais_fp8_dequantize_rows(self._h, _ptr(codes, torch.uint8, None, "codes", self.device),
+                                               codes.stride(0) if n_rows > 1 else vocab,
+                                               _ptr(scale, torch.float32, n_rows, "scale", self.device), n_rows,
+                                               vocab, _ptr(out), _dtype_code(out), vocab)
+        if rc != 0:
+            raise AisError(rc, "ais_fp8_dequantize_rows")
+        return out
+
+    def fp8_rollout_logprob(self, logits, token_ids, valid=None):
+        """-> logp_roll [R] fp32: log-softmax of the FP8 round trip of each row at the sampled token."""
+        n_rows, vocab, row_stride = _logits_geometry(logits)
+        out = torch.empty(n_rows, dtype=torch.float32, device=self.device)
+        self._sync_stream()
+        rc = self._lib.ais_fp8_rollout_logprob(
+            self._h, C.c_void_p(logits.data_ptr()), _dtype_code(logits), n_rows, vocab, row_stride,
+            _ptr(token_ids, torch.int32, n_rows, "token_ids", self.device),
+            _ptr(valid, torch.uint8, n_rows, "valid", self.device), _ptr(out))
+        if rc != 0:
+            raise AisError(rc, "ais_fp8_rollout_logprob")
+        return out
 
     # ------------------------------------------------------------------ helpers
     def read_diag(self, diag: torch.Tensor) -> dict:

@@ -21,6 +21,8 @@ struct DiagPartial {
   double su;      // sum of (w_bar - 1)
   double su2;     // sum of (w_bar - 1)^2
   double sabs;    // sum of |log pi_train - log pi_roll|
+  double sd;      // sum of (log pi_train - log pi_roll)
+  double sdp;     // sum of |pi_train - pi_roll|
   long long cnt;  // valid rows
   long long nclip;  // rows with rho > C
 };
@@ -81,5 +83,12 @@ int launch_row_coeff(ais_ctx* ctx, const float* logp_train, const float* logp_ro
                      const ais_diag* diag, const ais_params& p, const int* tile_off, int max_tiles,
                      double* partial, float* g_out, float* wtilde_out, double* loss_out);
 int launch_copy(ais_ctx* ctx, void* dst, const void* src, long long bytes);
+int launch_fp8_quantize(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,
+                        long long row_stride, unsigned char* codes, long long codes_stride, float* scale_out);
+int launch_fp8_dequantize(ais_ctx* ctx, const unsigned char* codes, long long codes_stride, const float* scale,
+                          long long n_rows, int vocab, void* out, ais_dtype dtype, long long out_stride);
+int launch_fp8_rollout_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,
+                               long long row_stride, const int* token_ids, const unsigned char* valid,
+                               float* logp_out);
 
 }  // namespace ais

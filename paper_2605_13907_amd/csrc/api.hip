@@ -280,6 +280,43 @@ int ais_grpo_loss_grad(ais_ctx* ctx, const void* logits, ais_dtype dtype, long l
                         params->inv_temperature, dlogits);
 }
 
+int ais_fp8_quantize_rows(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, long long vocab,
+                          long long row_stride, unsigned char* codes_out, long long codes_stride,
+                          float* scale_out) {
+  int rc = check_logits(logits, dtype, n_rows, vocab, row_stride);
+  if (rc != AIS_OK) return rc;
+  if (codes_stride < vocab) return AIS_ERR_STRIDE;
+  if (n_rows > 0 && (codes_out == nullptr || scale_out == nullptr)) return AIS_ERR_NULL;
+  if (ctx == nullptr) return AIS_ERR_NULL;
+  DeviceGuard guard(ctx->device);
+  return launch_fp8_quantize(ctx, logits, dtype, n_rows, (int)vocab, row_stride, codes_out, codes_stride,
+                             scale_out);
+}
+
+int ais_fp8_dequantize_rows(ais_ctx* ctx, const unsigned char* codes, long long codes_stride, const float* scale,
+                            long long n_rows, long long vocab, void* out, ais_dtype out_dtype,
+                            long long out_stride) {
+  int rc = check_logits(out, out_dtype, n_rows, vocab, out_stride);
+  if (rc != AIS_OK) return rc;
+  if (codes_stride < vocab) return AIS_ERR_STRIDE;
+  if (n_rows > 0 && (codes == nullptr || scale == nullptr)) return AIS_ERR_NULL;
+  if (ctx == nullptr) return AIS_ERR_NULL;
+  DeviceGuard guard(ctx->device);
+  return launch_fp8_dequantize(ctx, codes, codes_stride, scale, n_rows, (int)vocab, out, out_dtype, out_stride);
+}
+
+int ais_fp8_rollout_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, long long vocab,
+                            long long row_stride, const int* token_ids, const unsigned char* valid,
+                            float* logp_roll_out) {
+  int rc = check_logits(logits, dtype, n_rows, vocab, row_stride);
+  if (rc != AIS_OK) return rc;
+  if (n_rows > 0 && (token_ids == nullptr || logp_roll_out == nullptr)) return AIS_ERR_NULL;
+  if (ctx == nullptr) return AIS_ERR_NULL;
+  DeviceGuard guard(ctx->device);
+  return launch_fp8_rollout_logprob(ctx, logits, dtype, n_rows, (int)vocab, row_stride, token_ids, valid,
+                                    logp_roll_out);
+}
+
 int ais_profile(ais_ctx* ctx, int enable) {
   if (ctx == nullptr) return AIS_ERR_NULL;
   DeviceGuard guard(ctx->device);

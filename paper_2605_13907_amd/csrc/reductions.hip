@@ -105,15 +105,18 @@ __global__ __launch_bounds__(kTileThreads) void diag_partial_kernel(
   const long long r0 = lo + (long long)(b - tile_off[i]) * kTileRows;
   const long long r1 = min(hi, r0 + kTileRows);
   const double lnC = log((double)C);
-  double su = 0, su2 = 0, sabs = 0;
+  double su = 0, su2 = 0, sabs = 0, sd = 0, sdp = 0;
   long long cnt = 0, nclip = 0;
   for (long long n = r0 + threadIdx.x; n < r1; n += kTileThreads) {
     if (valid != nullptr && valid[n] == 0) continue;
-    const double d = (double)logp_train[n] - (double)logp_roll[n];      // log rho (Alg. 1, sampler-trainer ratio)
+    const double lt = (double)logp_train[n], lr = (double)logp_roll[n];
+    const double d = lt - lr;                                            // log rho (Alg. 1, sampler-trainer ratio)
     const double u = exp(fmin(d, lnC)) - 1.0;                            // w_bar - 1, w_bar = min(rho, C) (Eq. 10)
     su += u;
     su2 += u * u;
     sabs += fabs(d);
+    sd += d;
+    sdp += fabs(exp(lt) - exp(lr));
     cnt += 1;
     nclip += (d > lnC) ? 1 : 0;
   }
@@ -121,6 +124,8 @@ __global__ __launch_bounds__(kTileThreads) void diag_partial_kernel(
   p.su = block_sum(su, lds_d);
   p.su2 = block_sum(su2, lds_d);
   p.sabs = block_sum(sabs, lds_d);
+  p.sd = block_sum(sd, lds_d);
+  p.sdp = block_sum(sdp, lds_d);
   p.cnt = block_sum(cnt, lds_i);
   p.nclip = block_sum(nclip, lds_i);
   if (threadIdx.x == 0) partial[b] = p;
@@ -133,7 +138,7 @@ __global__ __launch_bounds__(kTileThreads) void diag_final_kernel(
     ais_diag* __restrict__ diag_out, const int* __restrict__ status) {
   __shared__ double lds_d[kTileThreads];
   __shared__ long long lds_i[kTileThreads];
-  double su = 0, su2 = 0, sabs = 0, sa = 0, sa2 = 0, saw = 0, saw2 = 0;
+  double su = 0, su2 = 0, sabs = 0, sd = 0, sdp = 0, sa = 0, sa2 = 0, saw = 0, saw2 = 0;
   long long cnt = 0, nclip = 0;
   for (int i = threadIdx.x; i < n_resp; i += kTileThreads) {
     // fold this response's tiles in order
@@ -143,6 +148,8 @@ __global__ __launch_bounds__(kTileThreads) void diag_final_kernel(
       r_su += partial[t].su;
       r_su2 += partial[t].su2;
       r_sabs += partial[t].sabs;
+      sd += partial[t].sd;
+      sdp += partial[t].sdp;
       r_cnt += partial[t].cnt;
       r_nclip += partial[t].nclip;
     }
@@ -176,6 +183,8 @@ __global__ __launch_bounds__(kTileThreads) void diag_final_kernel(
   su = block_sum(su, lds_d);
   su2 = block_sum(su2, lds_d);
   sabs = block_sum(sabs, lds_d);
+  sd = block_sum(sd, lds_d);
+  sdp = block_sum(sdp, lds_d);
   sa = block_sum(sa, lds_d);
   sa2 = block_sum(sa2, lds_d);
   saw = block_sum(saw, lds_d);
@@ -191,7 +200,7 @@ __global__ __launch_bounds__(kTileThreads) void diag_final_kernel(
   if (cnt == 0) {
     d.mean_w = d.var_w = d.cv2 = d.dbar = d.std_a = d.std_aw = d.dsigma = 0.0;
     d.ess_ratio = 1.0; d.alpha_ess = 1.0; d.alpha_mis = 0.0; d.alpha_var = 0.0; d.clip_frac = 0.0;
-    d.alpha = 0.0;
+    d.alpha = 0.0; d.kl_roll_train = 0.0; d.mean_abs_dp = 0.0;
   } else {
     const double N = (double)cnt;
     const double mu_u = su / N;
@@ -210,6 +219,8 @@ __global__ __launch_bounds__(kTileThreads) void diag_final_kernel(
     const double rel = fmin(1.0, fmax(0.0, d.alpha_ess - (double)p.beta_var * d.alpha_var));
     d.alpha = rel * d.alpha_mis;                              // Eq. 17
     d.clip_frac = (double)nclip / N;
+    d.kl_roll_train = -sd / N;       // tokens were drawn from pi_roll: mean of log pi_roll - log pi_train
+    d.mean_abs_dp = sdp / N;
   }
   if (p.alpha_override >= 0.f) d.alpha = (double)p.alpha_override;
   *diag_out = d;

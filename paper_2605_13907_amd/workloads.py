@@ -142,7 +142,10 @@ def e4m3_round_trip(x: torch.Tensor) -> torch.Tensor:
 
 def fp8_rollout_logits(z: torch.Tensor) -> torch.Tensor:
     """Per-row absmax-scaled E4M3 round trip of fp32 logits z [rows, V] (step 2 of the recipe)."""
-    s = z.abs().amax(dim=1, keepdim=True) / E4M3_MAX
+    amax = z.abs().amax(dim=1, keepdim=True)
+    # tensor / tensor is a true fp32 division on every device; tensor / python-scalar is evaluated on the GPU
+    # as a multiplication by the rounded reciprocal, which would make the scale depend on the device
+    s = amax / torch.full_like(amax, E4M3_MAX)
     s = torch.where(s > 0, s, torch.ones_like(s))
     return e4m3_round_trip(z / s) * s
 

@@ -240,6 +240,30 @@ def pin_diag_degenerate(O):
     assert out["n_valid"] == 0 and out["alpha"] == 0.0 and list(out["count"]) == [0, 0]
 
 
+def pin_mismatch_metrics(O):
+    """The two logged mismatch metrics (Sec. 3.1, the training-dynamics figure).  Closed form: every token has
+    pi_roll = 0.1; half of them pi_train = 0.3, half 0.1  =>  mean(log pi_roll - log pi_train) = -ln(3)/2 and
+    E|dp| = 0.1.  Statistically: on tokens drawn from pi_roll the KL estimate converges to the exact
+    KL(pi_roll || pi_train) of two small categorical distributions."""
+    n = 10
+    lr = np.full(n, math.log(0.1))
+    lt = np.where(np.arange(n) % 2 == 0, math.log(0.3), math.log(0.1))
+    out = O.diagnostics(lt, lr, None, np.array([0, n]), np.array([0.0]), O.Params())
+    assert abs(out["kl_roll_train"] + 0.5 * math.log(3.0)) < 1e-12
+    assert abs(out["mean_abs_dp"] - 0.1) < 1e-12
+    rng = np.random.default_rng(7)
+    p_roll = np.array([0.4, 0.25, 0.15, 0.1, 0.07, 0.03])
+    p_train = np.array([0.3, 0.3, 0.2, 0.05, 0.1, 0.05])
+    exact = float(np.sum(p_roll * np.log(p_roll / p_train)))
+    tok = rng.choice(6, size=200_000, p=p_roll)
+    out = O.diagnostics(np.log(p_train)[tok], np.log(p_roll)[tok], None, np.array([0, tok.size]), np.array([0.0]),
+                        O.Params())
+    sd = float(np.sqrt(np.sum(p_roll * np.log(p_roll / p_train) ** 2) - exact ** 2) / math.sqrt(tok.size))
+    assert exact > 0.01 and abs(out["kl_roll_train"] - exact) < 5 * sd
+    exact_dp = float(np.sum(p_roll * np.abs(p_train - p_roll)))
+    assert abs(out["mean_abs_dp"] - exact_dp) < 2e-3
+
+
 # --------------------------------------------------------------------------- O5
 def pin_mixed_weight_bounds(O):
     """Prop. 2: 0 <= 1 - alpha + alpha w_bar <= 1 + alpha (C - 1); alpha = 0 gives 1, alpha = 1 gives w_bar (Eq. 9)."""

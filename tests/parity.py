@@ -5,6 +5,7 @@ Tolerances (the bar this repository holds itself to):
   * log-prob, lse        |gpu - oracle| <= 2e-3 absolute on evaluated rows; exactly 0 on the others
   * n_valid, count[i], status, the set of rows with non-zero output: exact
   * mean_w, cv2, ess_ratio, dbar, std_a, std_aw, dsigma, alpha_ess, alpha_mis: relative 1e-3
+  * kl_roll_train (a signed mean that cancels): |d| <= 1e-3 * max(|ref|, dbar); mean_abs_dp: relative 1e-3
   * alpha_var, alpha (hard-thresholded, may sit at 0): |d| <= 1e-3 * max(|ref|, 1e-3)
   * loss: |d| <= 1e-3 * max(|ref|, floor), floor = (1/B) sum_i |A_i| mean_t(w_tilde) — the size of the terms
     whose cancellation (sum of a group's advantages is 0) produces the loss
@@ -90,6 +91,9 @@ def compare_scalars(ctx, out, ref, batch):
             rel_close(d[k], rd[k], floor=1e-9, what=k)
         rel_close(d["var_w"], rd["var_w"], floor=1e-9, what="var_w")
         rel_close(d["clip_frac"], rd["clip_frac"], floor=1e-9, what="clip_frac")
+        # the signed mean of d cancels: its natural scale is the mean of |d|
+        rel_close(d["kl_roll_train"], rd["kl_roll_train"], floor=rd["dbar"], what="kl_roll_train")
+        rel_close(d["mean_abs_dp"], rd["mean_abs_dp"], floor=1e-9, what="mean_abs_dp")
     rel_close(d["alpha_var"], rd["alpha_var"], floor=1e-3, what="alpha_var")
     rel_close(d["alpha"], rd["alpha"], floor=1e-3, what="alpha")
     wt = to_np64(out["wtilde"])

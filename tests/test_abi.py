@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_struct_sizes_match_header_layout():
     assert C.sizeof(B.AisParams) == 40          # 9 floats + 1 int
-    assert C.sizeof(B.AisDiag) == 8 + 13 * 8 + 8
+    assert C.sizeof(B.AisDiag) == 8 + 15 * 8 + 8
 
 
 def test_defaults_are_the_papers():

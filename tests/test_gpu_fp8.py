@@ -1,0 +1,112 @@
+"""GPU parity of the FP8-E4M3 rollout perturbation kernels against the CPU oracle (oracle/fp8_oracle.py).
+Codes and scales are byte / bit exact; the fused rollout log-prob is held to the log-prob tolerance."""
+import numpy as np
+import pytest
+import torch
+
+import oracle.fp8_oracle as F
+from paper_2605_13907_amd import binding as B
+from paper_2605_13907_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+LOGP_ATOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = B.AisContext()
+    yield c
+    c.close()
+
+
+def check_quant(ctx, z: torch.Tensor):
+    codes, scale = ctx.fp8_quantize_rows(z)
+    torch.cuda.synchronize()
+    zf = z.float().cpu().numpy()
+    ref_codes, ref_scale = F.quantize_rows(zf)
+    assert np.array_equal(scale.cpu().numpy(), ref_scale), "scales must be bit-exact"
+    got = codes.cpu().numpy()
+    if not np.array_equal(got, ref_codes):
+        bad = np.argwhere(got != ref_codes)
+        n, v = bad[0]
+        raise AssertionError(f"{len(bad)} codes differ; first at {n},{v}: z={zf[n, v]!r} s={ref_scale[n]!r} "
+                             f"gpu={got[n, v]:#x} oracle={ref_codes[n, v]:#x}")
+    for dt in (torch.float32, torch.bfloat16):
+        zr = ctx.fp8_dequantize_rows(codes, scale, dt)
+        torch.cuda.synchronize()
+        ref = torch.from_numpy(F.dequantize_rows(ref_codes, ref_scale)).to(dt)     # bf16: torch's RNE cast
+        assert torch.equal(zr.cpu(), ref), f"dequantised values differ ({dt})"
+    return codes, scale
+
+
+def test_every_code_tie_and_neighbour(ctx):
+    """A row whose abs-max is 448 has scale exactly 1, so the kernel's conversion is seen directly: every
+    representable value, every midpoint between neighbours (ties), and the fp32 values just around them."""
+    t = F.e4m3_decode_table()
+    vals = np.sort(np.array([v for v in t if not np.isnan(v)], dtype=np.float64))
+    mids = (vals[:-1] + vals[1:]) / 2
+    pts = np.concatenate([vals, mids]).astype(np.float32)
+    pts = np.concatenate([pts, np.nextafter(pts, np.float32(np.inf)), np.nextafter(pts, np.float32(-np.inf)),
+                          np.array([448.0, -448.0, 0.0, -0.0, 2.0 ** -10, -(2.0 ** -10), 1e-30, -1e-30], np.float32)])
+    pts = pts[np.abs(pts) <= 448.0]
+    row = torch.from_numpy(pts).cuda().unsqueeze(0).contiguous()
+    codes, scale = check_quant(ctx, row)
+    assert scale.item() == 1.0
+    # and the same values through the bf16 entry (those of them that bf16 represents)
+    check_quant(ctx, row.to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("vocab", [1, 7, 264, 1003, 4104, 20_008])
+def test_random_rows(ctx, dtype, vocab):
+    shape = W.RolloutShape("q", n_prompts=1, group_size=2, vocab=vocab, logits_dtype=dtype, sigma=3.0, boost=8.0,
+                           layout="packed", max_len=24, length_dist=("uniform", 9, 24), reward_p=0.5, seed=vocab + 1)
+    b = W.generate(shape, "cuda")
+    z = b.logits
+    z[0] = 0                      # an all-zero row: scale 1, codes 0
+    z[1, 0] = -37.5               # a negative abs-max
+    check_quant(ctx, z)
+    lp = ctx.fp8_rollout_logprob(z, b.token_ids, b.valid)
+    torch.cuda.synchronize()
+    ref = F.rollout_logprob(z.float().cpu().numpy(), b.token_ids.cpu().numpy())
+    assert np.abs(lp.double().cpu().numpy() - ref).max() <= LOGP_ATOL
+
+
+def test_pitch_and_misalignment(ctx):
+    z = torch.randn(9, 3016, device="cuda").mul_(3).to(torch.bfloat16)
+    check_quant(ctx, z[:, :3003])                         # row pitch > vocab, vector body + scalar tail
+    flat = torch.empty(9 * 3003 + 1, dtype=torch.bfloat16, device="cuda")
+    flat[1:] = z[:, :3003].reshape(-1)
+    check_quant(ctx, flat[1:].view(9, 3003))              # base not 16-byte aligned: element-wise path
+
+
+def test_rollout_logprob_equals_generator_and_masks(ctx):
+    """The device kernel reproduces the rollout log-probs the workload generator computed with torch ops."""
+    for k, kw in ((2, dict(vocab=20_008, len_div=32)), (3, dict(vocab=4104, len_div=4, n_prompts=2)), (1, {})):
+        b = W.generate(W.config(k).scaled(**kw) if kw else W.config(k), "cuda")
+        if b.shape.rollout_noise:
+            continue
+        lp = ctx.fp8_rollout_logprob(b.logits, b.token_ids, b.valid)
+        torch.cuda.synchronize()
+        off = b.valid == 0
+        assert bool((lp[off] == 0).all())
+        assert float((lp - b.logp_roll).abs().max()) <= LOGP_ATOL
+        assert ctx.status() == 0
+
+
+def test_full_size_rows_sampled(ctx):
+    """Workload 2 at full size: codes of sampled rows are bit-exact, scales of all rows are bit-exact."""
+    b = W.generate(W.config(2), "cuda", row_chunk=512)
+    codes, scale = ctx.fp8_quantize_rows(b.logits)
+    lp = ctx.fp8_rollout_logprob(b.logits, b.token_ids, b.valid)
+    torch.cuda.synchronize()
+    amax = b.logits.float().abs().amax(dim=1)
+    ref_scale = (amax.cpu().numpy().astype(np.float32) / np.float32(448.0)).astype(np.float32)
+    assert np.array_equal(scale.cpu().numpy(), ref_scale)
+    rows = np.unique(np.random.default_rng(0).integers(0, b.n_rows, size=40))
+    idx = torch.from_numpy(rows).cuda()
+    ref_codes, _ = F.quantize_rows(b.logits[idx].float().cpu().numpy())
+    assert np.array_equal(codes[idx].cpu().numpy(), ref_codes)
+    ref_lp = F.rollout_logprob(b.logits[idx].float().cpu().numpy(), b.token_ids[idx].cpu().numpy())
+    assert np.abs(lp[idx].double().cpu().numpy() - ref_lp).max() <= LOGP_ATOL
+    assert float((lp - b.logp_roll).abs().max()) <= LOGP_ATOL

@@ -40,6 +40,10 @@ MUTANTS = [
      "count = np.array([int(cu[i + 1] - cu[i]) for i in range(B)]"),
     ("a = _f64(adv)[seq][valid]                       # A broadcast to its tokens",
      "a = _f64(adv)[seq[::-1]][valid]"),
+    ('out["kl_roll_train"] = float((-d[valid]).mean())', 'out["kl_roll_train"] = float((d[valid]).mean())'),
+    ('out["kl_roll_train"] = float((-d[valid]).mean())', 'out["kl_roll_train"] = float(np.abs(d[valid]).mean())'),
+    ("np.abs(np.exp(logp_train[valid]) - np.exp(_f64(logp_roll)[valid])).mean()",
+     "np.abs(logp_train[valid] - _f64(logp_roll)[valid]).mean()"),
     # O5
     ("wt = 1.0 + alpha * (_f64(wbar) - 1.0)", "wt = 1.0 + alpha * _f64(wbar)"),
     ("wt = 1.0 + alpha * (_f64(wbar) - 1.0)", "wt = alpha + (1.0 - alpha) * _f64(wbar)"),
