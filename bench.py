@@ -80,6 +80,12 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = Qwen3-8B-shaped, V = 151,936)")
     ap.add_argument("--cpu-rows", type=int, default=6144, help="rows of the batch the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--in-place", action="store_true", help="write the gradient over the logits")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the FP8 rollout-perturbation kernels on the same batch (reported under next_rows)")
+    ap.add_argument("--mode", choices=["ais", "tis", "grpo"], default="ais",
+                    help="ais: adaptive alpha (the paper's method); tis: alpha forced to 1; grpo: alpha forced to 0")
+    ap.add_argument("--stale-old", action="store_true",
+                    help="pass a perturbed log pi_old so that the clipped surrogate's gate is exercised")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the path has no inter-GPU step; run with --gpus 1", file=sys.stderr)
@@ -99,15 +105,24 @@ def main():
     N = batch.n_valid
     e = batch.logits.element_size()
     ctx = binding.AisContext()
-    p = binding.default_params()
+    p = binding.default_params(alpha_override={"ais": -1.0, "tis": 1.0, "grpo": 0.0}[args.mode])
     dz = batch.logits if args.in_place else torch.empty_like(batch.logits)
+    logp_old = None
+    if args.stale_old:       # torch's log_softmax stands in for the trainer's earlier log-probs (not timed)
+        logp_old = torch.empty(R, dtype=torch.float32, device="cuda")
+        gen_old = torch.Generator(device="cuda").manual_seed(17)
+        for r0 in range(0, R, 512):
+            z = batch.logits[r0:r0 + 512].float()
+            tok = batch.token_ids[r0:r0 + 512].long().clamp(min=0).unsqueeze(1)
+            logp_old[r0:r0 + 512] = torch.log_softmax(z, 1).gather(1, tok).squeeze(1)
+        logp_old += 0.2 * torch.randn(R, device="cuda", generator=gen_old)
 
     def step():
         logp, lse = ctx.token_logprob(batch.logits, batch.token_ids, batch.valid, p.inv_temperature)
         adv, count, diag = ctx.diagnostics(logp, batch.logp_roll, batch.valid, batch.cu_rows, batch.rewards,
                                            shape.group_size, p)
         return ctx.grpo_loss_grad(batch.logits, batch.token_ids, batch.valid, batch.cu_rows, logp, lse,
-                                  batch.logp_roll, adv, count, diag, p, dlogits=dz), diag
+                                  batch.logp_roll, adv, count, diag, p, logp_old=logp_old, dlogits=dz), diag
 
     if args.in_place:
         keep = batch.logits.clone()
@@ -155,7 +170,8 @@ def main():
         "dtype": "f32" if shape.logits_dtype == "f32" else "f32 (bf16 storage)", "data": "synthetic",
         "config": {"workload": f"config {args.config}: {shape.name}", "vocab": V, "rows": R, "valid_rows": N,
                    "responses": shape.n_resp, "group_size": shape.group_size, "logits": shape.logits_dtype,
-                   "layout": shape.layout, "in_place": bool(args.in_place)},
+                   "layout": shape.layout, "in_place": bool(args.in_place), "mode": args.mode,
+                   "stale_old_policy": bool(args.stale_old)},
         "roofline": {"bound": "hbm", "kernel": "dlogits_kernel", "achieved": bwd_gbps, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": bwd_gbps / HBM_PEAK_GBPS,
                      "traffic": measured_traffic("dlogits_kernel", args.config),
@@ -168,6 +184,47 @@ def main():
         "diag": {k: d[k] for k in ("alpha", "alpha_ess", "alpha_mis", "alpha_var", "dbar", "ess_ratio")},
         "loss": float(loss.item()), "gen_s": t_gen,
     }
+    if args.extras:
+        ctx.profile(True)
+        for _ in range(3):
+            codes, scale = ctx.fp8_quantize_rows(batch.logits)
+            ctx.fp8_dequantize_rows(codes, scale, batch.logits.dtype)
+            ctx.fp8_rollout_logprob(batch.logits, batch.token_ids, batch.valid)
+        extras = {}
+        for name, which, nbytes in (("fp8_quantize_rows", binding.AIS_K_FP8_QUANT, (e + 1) * V * R),
+                                    ("fp8_dequantize_rows", binding.AIS_K_FP8_DEQUANT, (e + 1) * V * R),
+                                    ("fp8_rollout_logprob", binding.AIS_K_FP8_LOGPROB, e * V * N)):
+            ms, n = ctx.profile_read(which)
+            extras[name] = {"avg_ms": ms / n, "algorithmic_bytes": nbytes, "GB/s": nbytes / (ms / n * 1e-3) / 1e9,
+                            "frac": nbytes / (ms / n * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+        ctx.profile(False)
+        del codes, scale
+        # one-sweep variant (direction + per-row scale): each row read once, 2 e V bytes per valid token
+        def one_sweep():
+            logp, lse, sg = ctx.token_logprob_softmax_grad(batch.logits, batch.token_ids, batch.valid,
+                                                           p.inv_temperature, sgrad=dz)
+            adv, count, diag = ctx.diagnostics(logp, batch.logp_roll, batch.valid, batch.cu_rows, batch.rewards,
+                                               shape.group_size, p)
+            return ctx.grpo_row_scale(logp, batch.logp_roll, batch.valid, batch.cu_rows, adv, count, diag, p,
+                                      logp_old)
+        for _ in range(2):
+            one_sweep()
+        torch.cuda.synchronize()
+        ctx.profile(True)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            one_sweep()
+        torch.cuda.synchronize()
+        ms_os = (time.perf_counter() - t0) / args.steps * 1e3
+        ms_k, n_k = ctx.profile_read(binding.AIS_K_FUSED)
+        ctx.profile(False)
+        os_bytes = 2 * e * V * N + e * V * (R - N)
+        extras["one_sweep_path"] = {"ms_per_step": ms_os, "tokens/s": N / (ms_os * 1e-3),
+                                    "algorithmic_bytes": os_bytes, "GB/s": os_bytes / (ms_os * 1e-3) / 1e9,
+                                    "frac": os_bytes / (ms_os * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                                    "fused_kernel_avg_ms": (ms_k / n_k) if n_k else None,
+                                    "speedup_vs_three_call_path": ms_step / ms_os}
+        result["next_rows"] = extras
     if args.cpu_rows > 0:
         params = dict(C=p.C, delta=p.delta, gamma=p.gamma, eps_std=p.eps_std, beta_var=p.beta_var,
                       clip_eps=p.clip_eps)

@@ -190,6 +190,34 @@ int ais_grpo_loss_grad(ais_ctx* ctx, const void* logits, ais_dtype dtype, long l
                        const int* count, const ais_diag* diag, const ais_params* params,
                        float* wtilde_out, double* loss_out, void* dlogits);
 
+/* ---- one-sweep variant: unscaled gradient direction plus a per-row scale -------------------------- */
+
+/* The mixing coefficient alpha enters the gradient of Eq. 19 only through one scalar per row:
+ * dlogits[n, :] = g[n] * s[n, :] with s[n, v] = softmax(inv_temperature z_n)_v - 1[v = y_n].  This pair of
+ * calls emits s in the same sweep that computes the log-probs, and g after the diagnostics, so that each
+ * logits row is read from HBM once (2 e V bytes per token in total instead of 3 e V); a consumer such as
+ * the LM-head backward folds g[n] into its own operands.
+ *
+ * ais_token_logprob_softmax_grad: as ais_token_logprob, and additionally
+ *   sgrad_out  [n_rows, row_stride] of `dtype`: s on evaluated rows, 0 on the others; may be the same
+ *              buffer as `logits` (in place).  Rows are held in the register file of one compute unit
+ *              (up to 196,608 bf16 or 98,304 fp32 elements, 16-byte aligned); wider or unaligned rows
+ *              are processed in two passes with the same results.
+ * ais_grpo_row_scale: as ais_grpo_loss_grad without the logits; writes
+ *   g_out      [n_rows] fp32: the derivative of the loss w.r.t. the row's log-probability times
+ *              inv_temperature (0 on rows not evaluated or clipped away), so that g_out[n] * s[n, :] equals
+ *              the dlogits of ais_grpo_loss_grad up to rounding
+ *   wtilde_out, loss_out as in ais_grpo_loss_grad. */
+int ais_token_logprob_softmax_grad(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows,
+                                   long long vocab, long long row_stride, const int* token_ids,
+                                   const unsigned char* valid, float inv_temperature, float* logp_out,
+                                   float* lse_out, void* sgrad_out);
+int ais_grpo_row_scale(ais_ctx* ctx, const float* logp_train, const float* logp_roll, const float* logp_old,
+                       const float* logp_ref, const unsigned char* valid, long long n_rows,
+                       const long long* cu_rows, int n_resp, const float* adv, const int* count,
+                       const ais_diag* diag, const ais_params* params, float* wtilde_out,
+                       double* loss_out, float* g_out);
+
 /* ---- the rollout-side FP8 perturbation (input generation on the device) ------------------------ */
 
 /* Per-row FP8-E4M3 quantisation of logits: the symmetric scaling of Eq. 1 with the E4M3 value grid
@@ -222,7 +250,7 @@ int ais_fp8_rollout_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, l
 /* Kernels whose device time can be read back. */
 typedef enum ais_kernel {
   AIS_K_LOGPROB = 0, AIS_K_DLOGITS = 1, AIS_K_COPY = 2, AIS_K_FP8_QUANT = 3, AIS_K_FP8_DEQUANT = 4,
-  AIS_K_FP8_LOGPROB = 5, AIS_K_COUNT_ = 6
+  AIS_K_FP8_LOGPROB = 5, AIS_K_FUSED = 6, AIS_K_COUNT_ = 7
 } ais_kernel;
 
 /* With `enable` != 0 every launch of the kernels above is bracketed by HIP events on the

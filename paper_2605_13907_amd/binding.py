@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(PKG, "libais_gfx950.so")
 
 AIS_BF16, AIS_F32 = 0, 1
 AIS_K_LOGPROB, AIS_K_DLOGITS, AIS_K_COPY, AIS_K_FP8_QUANT, AIS_K_FP8_DEQUANT, AIS_K_FP8_LOGPROB = range(6)
+AIS_K_FUSED = 6
 STATUS_BAD_TOKEN, STATUS_BAD_CU = 1, 2
 
 ERRORS = {
@@ -67,6 +68,8 @@ SYMBOLS = {
     "ais_diagnostics": (_I, [_P, _P, _P, _P, _LL, _P, _I, _I, _P, C.POINTER(AisParams), _P, _P, _P]),
     "ais_grpo_loss_grad": (_I, [_P, _P, _I, _LL, _LL, _LL, _P, _P, _P, _I, _P, _P, _P, _P, _P, _P, _P, _P,
                                 C.POINTER(AisParams), _P, _P, _P]),
+    "ais_token_logprob_softmax_grad": (_I, [_P, _P, _I, _LL, _LL, _LL, _P, _P, _F, _P, _P, _P]),
+    "ais_grpo_row_scale": (_I, [_P, _P, _P, _P, _P, _P, _LL, _P, _I, _P, _P, _P, C.POINTER(AisParams), _P, _P, _P]),
     "ais_fp8_quantize_rows": (_I, [_P, _P, _I, _LL, _LL, _LL, _P, _LL, _P]),
     "ais_fp8_dequantize_rows": (_I, [_P, _P, _LL, _P, _LL, _LL, _P, _I, _LL]),
     "ais_fp8_rollout_logprob": (_I, [_P, _P, _I, _LL, _LL, _LL, _P, _P, _P]),
@@ -243,6 +246,59 @@ class AisContext:
                                                batch.logp_roll, adv, count, diag, p, logp_old, logp_ref,
                                                dlogits=batch.logits if in_place else None)
         return dict(logp=logp, lse=lse, adv=adv, count=count, diag=diag, loss=loss, wtilde=wtilde, dlogits=dz)
+
+    # ------------------------------------------------------------------ one-sweep variant
+    def token_logprob_softmax_grad(self, logits, token_ids, valid=None, inv_temperature: float = 1.0, sgrad=None):
+        """-> (logp, lse, sgrad) with sgrad[n, v] = softmax_v - 1[v = y_n]; pass sgrad=logits for in place."""
+        n_rows, vocab, row_stride = _logits_geometry(logits)
+        dev = self.device
+        logp = torch.empty(n_rows, dtype=torch.float32, device=dev)
+        lse = torch.empty(n_rows, dtype=torch.float32, device=dev)
+        if sgrad is None:
+            sgrad = torch.empty_strided(logits.shape, logits.stride(), dtype=logits.dtype, device=dev)
+        elif sgrad.dtype != logits.dtype or sgrad.shape != logits.shape or sgrad.stride() != logits.stride():
+            raise ValueError("sgrad must have the dtype, shape and strides of logits")
+        self._sync_stream()
+        rc = self._lib.ais_token_logprob_softmax_grad(
+            self._h, C.c_void_p(logits.data_ptr()), _dtype_code(logits), n_rows, vocab, row_stride,
+            _ptr(token_ids, torch.int32, n_rows, "token_ids", dev), _ptr(valid, torch.uint8, n_rows, "valid", dev),
+            float(inv_temperature), _ptr(logp), _ptr(lse), C.c_void_p(sgrad.data_ptr()))
+        if rc != 0:
+            raise AisError(rc, "ais_token_logprob_softmax_grad")
+        return logp, lse, sgrad
+
+    def grpo_row_scale(self, logp_train, logp_roll, valid, cu_rows, adv, count, diag,
+                       params: Optional[AisParams] = None, logp_old=None, logp_ref=None):
+        """-> (loss [1] fp64, wtilde [R], g [R]) with dlogits[n, :] = g[n] * sgrad[n, :]."""
+        p = params or default_params()
+        dev = self.device
+        n_rows, n_resp = logp_train.numel(), adv.numel()
+        wtilde = torch.empty(n_rows, dtype=torch.float32, device=dev)
+        g = torch.empty(n_rows, dtype=torch.float32, device=dev)
+        loss = torch.empty(1, dtype=torch.float64, device=dev)
+        self._sync_stream()
+        rc = self._lib.ais_grpo_row_scale(
+            self._h, _ptr(logp_train, torch.float32, n_rows, "logp_train", dev),
+            _ptr(logp_roll, torch.float32, n_rows, "logp_roll", dev),
+            _ptr(logp_old, torch.float32, n_rows, "logp_old", dev),
+            _ptr(logp_ref, torch.float32, n_rows, "logp_ref", dev), _ptr(valid, torch.uint8, n_rows, "valid", dev),
+            n_rows, _ptr(cu_rows, torch.int64, n_resp + 1, "cu_rows", dev), n_resp,
+            _ptr(adv, torch.float32, n_resp, "adv", dev), _ptr(count, torch.int32, n_resp, "count", dev),
+            _ptr(diag, torch.uint8, C.sizeof(AisDiag), "diag", dev), C.byref(p), _ptr(wtilde), _ptr(loss), _ptr(g))
+        if rc != 0:
+            raise AisError(rc, "ais_grpo_row_scale")
+        return loss, wtilde, g
+
+    def step_one_sweep(self, batch, params: Optional[AisParams] = None, logp_old=None, logp_ref=None, in_place=False):
+        """The path with each logits row read once: direction s and per-row scale g instead of dlogits."""
+        p = params or default_params()
+        logp, lse, s = self.token_logprob_softmax_grad(batch.logits, batch.token_ids, batch.valid, p.inv_temperature,
+                                                       sgrad=batch.logits if in_place else None)
+        adv, count, diag = self.diagnostics(logp, batch.logp_roll, batch.valid, batch.cu_rows, batch.rewards,
+                                            batch.shape.group_size, p)
+        loss, wtilde, g = self.grpo_row_scale(logp, batch.logp_roll, batch.valid, batch.cu_rows, adv, count, diag, p,
+                                              logp_old, logp_ref)
+        return dict(logp=logp, lse=lse, adv=adv, count=count, diag=diag, loss=loss, wtilde=wtilde, sgrad=s, g=g)
 
     # ------------------------------------------------------------------ FP8 rollout perturbation
     def fp8_quantize_rows(self, logits):

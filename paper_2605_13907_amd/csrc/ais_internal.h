@@ -70,8 +70,12 @@ int launch_token_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, long
                          long long row_stride, const int* token_ids, const unsigned char* valid,
                          float inv_temperature, float* logp_out, float* lse_out);
 int launch_dlogits(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,
-                   long long row_stride, const int* token_ids, const float* g, const float* lse,
-                   const float* logp, float inv_temperature, void* dlogits);
+                   long long row_stride, const int* token_ids, const float* g, const unsigned char* valid,
+                   const float* lse, const float* logp, float inv_temperature, void* dlogits);
+int launch_fused_logprob_softmax(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,
+                                 long long row_stride, const int* token_ids, const unsigned char* valid,
+                                 float inv_temperature, float* logp_out, float* lse_out, void* sgrad,
+                                 bool* used_registers);
 int launch_plan(ais_ctx* ctx, const long long* cu_rows, int n_resp, long long n_rows, int* tile_off, int max_tiles);
 int launch_diagnostics(ais_ctx* ctx, const float* logp_train, const float* logp_roll, const unsigned char* valid,
                        long long n_rows, const long long* cu_rows, int n_resp, int group_size,
@@ -81,7 +85,7 @@ int launch_row_coeff(ais_ctx* ctx, const float* logp_train, const float* logp_ro
                      const float* logp_ref, const unsigned char* valid, long long n_rows,
                      const long long* cu_rows, int n_resp, const float* adv, const int* count,
                      const ais_diag* diag, const ais_params& p, const int* tile_off, int max_tiles,
-                     double* partial, float* g_out, float* wtilde_out, double* loss_out);
+                     double* partial, float* g_out, float* wtilde_out, double* loss_out, float g_scale);
 int launch_copy(ais_ctx* ctx, void* dst, const void* src, long long bytes);
 int launch_fp8_quantize(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,
                         long long row_stride, unsigned char* codes, long long codes_stride, float* scale_out);

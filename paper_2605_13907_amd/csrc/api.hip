@@ -274,10 +274,60 @@ int ais_grpo_loss_grad(ais_ctx* ctx, const void* logits, ais_dtype dtype, long l
   if (rc != AIS_OK) return rc;
   rc = launch_row_coeff(ctx, logp_train, logp_roll, logp_old, logp_ref, valid, n_rows, cu_rows, n_resp, adv, count,
                         diag, *params, tile_off, w.max_tiles, reinterpret_cast<double*>(ws + w.partial), g,
-                        wtilde_out, loss_out);
+                        wtilde_out, loss_out, 1.0f);
   if (rc != AIS_OK) return rc;
-  return launch_dlogits(ctx, logits, dtype, n_rows, (int)vocab, row_stride, token_ids, g, lse, logp_train,
+  return launch_dlogits(ctx, logits, dtype, n_rows, (int)vocab, row_stride, token_ids, g, nullptr, lse, logp_train,
                         params->inv_temperature, dlogits);
+}
+
+int ais_token_logprob_softmax_grad(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows,
+                                   long long vocab, long long row_stride, const int* token_ids,
+                                   const unsigned char* valid, float inv_temperature, float* logp_out,
+                                   float* lse_out, void* sgrad_out) {
+  int rc = check_logits(logits, dtype, n_rows, vocab, row_stride);
+  if (rc != AIS_OK) return rc;
+  if (n_rows > 0 && (token_ids == nullptr || logp_out == nullptr || lse_out == nullptr || sgrad_out == nullptr))
+    return AIS_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(sgrad_out) % (dtype == AIS_BF16 ? 2 : 4) != 0) return AIS_ERR_ALIGN;
+  if (!std::isfinite(inv_temperature) || inv_temperature <= 0.f) return AIS_ERR_PARAM;
+  if (ctx == nullptr) return AIS_ERR_NULL;
+  DeviceGuard guard(ctx->device);
+  bool used = false;
+  rc = launch_fused_logprob_softmax(ctx, logits, dtype, n_rows, (int)vocab, row_stride, token_ids, valid,
+                                    inv_temperature, logp_out, lse_out, sgrad_out, &used);
+  if (rc != AIS_OK || used) return rc;
+  // the row does not fit the register file: two passes (log-probs, then the direction with unit coefficient)
+  rc = launch_token_logprob(ctx, logits, dtype, n_rows, (int)vocab, row_stride, token_ids, valid, inv_temperature,
+                            logp_out, lse_out);
+  if (rc != AIS_OK) return rc;
+  return launch_dlogits(ctx, logits, dtype, n_rows, (int)vocab, row_stride, token_ids, nullptr, valid, lse_out,
+                        logp_out, inv_temperature, sgrad_out);
+}
+
+int ais_grpo_row_scale(ais_ctx* ctx, const float* logp_train, const float* logp_roll, const float* logp_old,
+                       const float* logp_ref, const unsigned char* valid, long long n_rows,
+                       const long long* cu_rows, int n_resp, const float* adv, const int* count,
+                       const ais_diag* diag, const ais_params* params, float* wtilde_out, double* loss_out,
+                       float* g_out) {
+  int rc = check_batch(n_rows, n_resp, 1);
+  if (rc != AIS_OK) return rc;
+  rc = check_params(params);
+  if (rc != AIS_OK) return rc;
+  if (cu_rows == nullptr || adv == nullptr || count == nullptr || diag == nullptr || loss_out == nullptr)
+    return AIS_ERR_NULL;
+  if (n_rows > 0 && (logp_train == nullptr || logp_roll == nullptr || g_out == nullptr)) return AIS_ERR_NULL;
+  if (ctx == nullptr) return AIS_ERR_NULL;
+  DeviceGuard guard(ctx->device);
+  const WorkspaceLayout w = workspace_layout(n_rows, n_resp);
+  rc = ensure_workspace(ctx, w.total);
+  if (rc != AIS_OK) return rc;
+  char* ws = static_cast<char*>(ctx->ws);
+  int* tile_off = reinterpret_cast<int*>(ws + w.tile_off);
+  rc = launch_plan(ctx, cu_rows, n_resp, n_rows, tile_off, w.max_tiles);
+  if (rc != AIS_OK) return rc;
+  return launch_row_coeff(ctx, logp_train, logp_roll, logp_old, logp_ref, valid, n_rows, cu_rows, n_resp, adv, count,
+                          diag, *params, tile_off, w.max_tiles, reinterpret_cast<double*>(ws + w.partial), g_out,
+                          wtilde_out, loss_out, params->inv_temperature);
 }
 
 int ais_fp8_quantize_rows(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, long long vocab,

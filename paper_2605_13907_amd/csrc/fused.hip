@@ -1,0 +1,241 @@
+// One-sweep variant of the two vocabulary passes: each logits row is read from HBM once, kept in the
+// register file of one compute unit while its log-sum-exp is formed, and written back as the unscaled
+// gradient direction  s[n, v] = softmax(z_n / T)_v - 1[v = y_n].
+//
+// The mixing coefficient alpha (Eq. 17) depends on every row of the batch, so the final gradient of
+// Eq. 19 cannot be written in the same sweep that computes the log-probs; but alpha enters that gradient
+// only through one scalar per row: dz[n, :] = g_n * s[n, :].  Emitting s and, after the diagnostics, the
+// per-row scale g_n lets the consumer (the LM-head backward) fold g_n into its own operands, and the path
+// moves 2 * e * V bytes per token instead of 3 * e * V.
+//
+// A 151,936-wide bf16 row is 297 KiB; a CDNA4 compute unit has 512 KiB of vector registers.  One
+// workgroup of 1,024 threads (16 wavefronts, 4 per SIMD, up to 128 registers per lane) holds the row as
+// NV 16-byte vectors per lane.  All NV loads of a lane are issued back to back, so the whole row is in
+// flight at once and memory latency is paid once per row.  Rows too wide for the register file fall back
+// to the two-pass kernels.
+#include "ais_internal.h"
+#include "device_utils.h"
+
+namespace ais {
+namespace {
+
+using namespace dev;
+
+constexpr int kRowThreads = 1024;
+constexpr int kRowWaves = kRowThreads / 64;
+
+template <typename T> __device__ __forceinline__ u32x4 lowest_fill();
+template <> __device__ __forceinline__ u32x4 lowest_fill<bf16_t>() {
+  return u32x4{0xff7fff7fu, 0xff7fff7fu, 0xff7fff7fu, 0xff7fff7fu};   // pairs of the most negative finite bf16
+}
+template <> __device__ __forceinline__ u32x4 lowest_fill<float>() {
+  return u32x4{0xff7fffffu, 0xff7fffffu, 0xff7fffffu, 0xff7fffffu};   // -FLT_MAX
+}
+
+// q with its element `sub` replaced by the most negative finite value of the type.
+template <typename T> __device__ __forceinline__ u32x4 patch_lowest(u32x4 q, int sub);
+template <> __device__ __forceinline__ u32x4 patch_lowest<bf16_t>(u32x4 q, int sub) {
+  const uint32_t keep = (sub & 1) ? 0x0000ffffu : 0xffff0000u;
+  const uint32_t put = (sub & 1) ? 0xff7f0000u : 0x0000ff7fu;
+#pragma unroll
+  for (int w = 0; w < 4; ++w)
+    if (w == (sub >> 1)) q[w] = (q[w] & keep) | put;
+  return q;
+}
+template <> __device__ __forceinline__ u32x4 patch_lowest<float>(u32x4 q, int sub) {
+#pragma unroll
+  for (int w = 0; w < 4; ++w)
+    if (w == sub) q[w] = 0xff7fffffu;
+  return q;
+}
+
+// grid.x = n_rows, block = kRowThreads.  Requires 16-byte aligned rows and vocab / N <= NV * kRowThreads.
+template <typename T, int NV>
+__global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
+    const T* logits, long long row_stride, int vocab, const int* __restrict__ token_ids,
+    const unsigned char* __restrict__ valid, float inv_temperature, float* __restrict__ logp_out,
+    float* __restrict__ lse_out, T* sgrad, int* __restrict__ status) {
+  constexpr int N = Vec<T>::N;
+  __shared__ MaxSum lds[kRowWaves];
+  __shared__ float lds_row[2];          // shift (= -lse * log2e) and the sampled token's element
+  const long long row = blockIdx.x;
+  const int tid = threadIdx.x;
+  const T* zr = logits + row * row_stride;
+  T* sr = sgrad + row * row_stride;
+  const int nvec = vocab / N;
+  const int tail = vocab - nvec * N;    // < N elements, one per thread for the first `tail` threads
+  u32x4* sv = reinterpret_cast<u32x4*>(sr);
+
+  if (valid != nullptr && valid[row] == 0) {     // not evaluated: no read, zero direction
+    if (tid == 0) {
+      logp_out[row] = 0.f;
+      lse_out[row] = 0.f;
+    }
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int i = tid + k * kRowThreads;
+      if (i < nvec) store_stream(sv + i, zero);
+    }
+    if (tid < tail) Vec<T>::store1(sr + nvec * N + tid, 0.f);
+    return;
+  }
+
+  // ---- phase 1: the whole row into registers ----
+  const u32x4* zv = reinterpret_cast<const u32x4*>(zr);
+  u32x4 q[NV];
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int i = tid + k * kRowThreads;
+    q[k] = (i < nvec) ? load_stream(zv + i) : lowest_fill<T>();
+  }
+  float xt = (tid < tail) ? Vec<T>::load1(zr + nvec * N + tid) : kNegHuge;   // kNegHuge contributes 0
+
+  const float scale = inv_temperature * kLog2e;
+  const int y = token_ids[row];
+  const bool y_ok = (y >= 0) && (y < vocab);
+  const float zy = y_ok ? Vec<T>::load1(zr + y) : 0.f;
+  // where this thread holds the sampled token: vector slot k and lane element, or the tail register
+  const int yv = (y_ok && y < nvec * N) ? y / N : -1;
+  const int yk = (yv >= 0 && yv % kRowThreads == tid) ? yv / kRowThreads : -1;
+  const int ysub = y % N;
+  const bool y_in_tail = y_ok && y >= nvec * N && (y - nvec * N) == tid;
+
+  // The sampled token's own term is kept out of the running sum (see token_logprob_kernel).  Its element
+  // is overwritten, in the packed registers, by the most negative finite value: one lane of one wavefront
+  // takes this branch, the sweeps below stay free of control flow.
+  if (yk >= 0) {
+#pragma unroll
+    for (int k = 0; k < NV; ++k)
+      if (k == yk) q[k] = patch_lowest<T>(q[k], ysub);
+  }
+  if (y_in_tail) xt = kNegHuge;
+
+  // ---- phase 1: running (max, sum) over the row, one vector at a time ----
+  MaxSum st{kNegHuge, 0.f};
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    float x[N];
+    Vec<T>::unpack(q[k], x);
+    accumulate<N>(x, scale, st);
+    __builtin_amdgcn_sched_barrier(0);   // keeps the unpacked values of one vector short-lived
+  }
+  accumulate<1>(&xt, scale, st);
+  // The row stays in registers in its packed form: the empty asm makes each vector opaque, so that the
+  // unpacked fp32 values of phase 1 are not kept alive for phase 2 (four times the registers).
+#pragma unroll
+  for (int k = 0; k < NV; ++k) asm volatile("" : "+v"(q[k]));
+  st = wave_merge(st);
+  if ((tid & 63) == 0) lds[tid >> 6] = st;
+  __syncthreads();
+  if (tid == 0) {
+    MaxSum t = lds[0];
+#pragma unroll
+    for (int w = 1; w < kRowWaves; ++w) t = merge(t, lds[w]);
+    float lse, logp;
+    if (y_ok) {
+      const double r = (double)t.s * exp2((double)t.m - (double)zy * (double)scale);
+      const double l1p = log1p(r);
+      logp = (float)(-l1p);
+      lse = (float)((double)zy * (double)inv_temperature + l1p);
+    } else {
+      lse = (t.m + log2_fast(t.s)) * kLn2;
+      logp = 0.f;
+      atomicOr(status, AIS_STATUS_BAD_TOKEN);
+    }
+    logp_out[row] = logp;
+    lse_out[row] = lse;
+    lds_row[0] = -lse * kLog2e;
+    lds_row[1] = expm1f(logp);            // p_y - 1 without cancellation
+  }
+  __syncthreads();
+  const float shift = lds_row[0];
+  const float sy = lds_row[1];
+
+  // ---- phase 2: softmax from the registers (the patched element comes out as 0) ----
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int i = tid + k * kRowThreads;
+    float x[N];
+    Vec<T>::unpack(q[k], x);
+#pragma unroll
+    for (int j = 0; j < N; ++j) x[j] = exp2_fast(__builtin_fmaf(x[j], scale, shift));
+    if (i < nvec) store_stream(sv + i, Vec<T>::pack(x));
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  if (tid < tail) Vec<T>::store1(sr + nvec * N + tid, exp2_fast(__builtin_fmaf(xt, scale, shift)));
+  // the sampled token's element p_y - 1, by the lane that owns it, after its vector store has completed
+  if (yk >= 0 || y_in_tail) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    Vec<T>::store1(sr + y, sy);
+  }
+}
+
+template <typename T, int NV>
+void launch_nv(ais_ctx* ctx, const T* z, long long n_rows, int vocab, long long row_stride, const int* token_ids,
+               const unsigned char* valid, float inv_t, float* logp, float* lse, T* sgrad) {
+  fused_logprob_softmax_kernel<T, NV><<<dim3((unsigned)n_rows), dim3(kRowThreads), 0, ctx->stream>>>(
+      z, row_stride, vocab, token_ids, valid, inv_t, logp, lse, sgrad, ctx->status_dev);
+}
+
+// Vectors per lane needed for a row, or 0 when the row cannot be held (too wide, or not 16-byte aligned).
+template <typename T>
+int vectors_per_lane(const void* z, const void* s, int vocab, long long row_stride) {
+  constexpr int N = Vec<T>::N;
+  const bool ok16 = reinterpret_cast<uintptr_t>(z) % 16 == 0 && reinterpret_cast<uintptr_t>(s) % 16 == 0 &&
+                    (row_stride * (long long)sizeof(T)) % 16 == 0;
+  const int need = (vocab / N + kRowThreads - 1) / kRowThreads;
+  return (ok16 && need <= 24) ? (need < 1 ? 1 : need) : 0;
+}
+
+template <typename T>
+void launch_typed(ais_ctx* ctx, int need, const void* logits, long long n_rows, int vocab, long long row_stride,
+                  const int* token_ids, const unsigned char* valid, float inv_t, float* logp, float* lse,
+                  void* sgrad) {
+  const T* z = static_cast<const T*>(logits);
+  T* s = static_cast<T*>(sgrad);
+  // NV is a compile-time constant (the row lives in named registers); sizes near the register limit get an
+  // exact instantiation so that common vocabularies (e.g. 151,936 -> 19 vectors per lane) do not spill
+#define AIS_FUSED_CASE(NVAL)                                                                                 \
+  if (need <= NVAL) {                                                                                        \
+    launch_nv<T, NVAL>(ctx, z, n_rows, vocab, row_stride, token_ids, valid, inv_t, logp, lse, s);            \
+    return;                                                                                                  \
+  }
+  AIS_FUSED_CASE(4)
+  AIS_FUSED_CASE(8)
+  AIS_FUSED_CASE(12)
+  AIS_FUSED_CASE(16)
+  AIS_FUSED_CASE(17)
+  AIS_FUSED_CASE(18)
+  AIS_FUSED_CASE(19)
+  AIS_FUSED_CASE(20)
+  AIS_FUSED_CASE(21)
+  AIS_FUSED_CASE(22)
+  AIS_FUSED_CASE(23)
+  AIS_FUSED_CASE(24)
+#undef AIS_FUSED_CASE
+}
+
+}  // namespace
+
+// Sets *used_registers to false (and launches nothing) when the row does not fit the register file or is
+// not 16-byte aligned; the caller then runs the two-pass kernels.
+int launch_fused_logprob_softmax(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,
+                                 long long row_stride, const int* token_ids, const unsigned char* valid,
+                                 float inv_temperature, float* logp_out, float* lse_out, void* sgrad,
+                                 bool* used_registers) {
+  const int need = dtype == AIS_BF16 ? vectors_per_lane<bf16_t>(logits, sgrad, vocab, row_stride)
+                                     : vectors_per_lane<float>(logits, sgrad, vocab, row_stride);
+  *used_registers = need > 0;
+  if (need == 0 || n_rows == 0) return AIS_OK;
+  ScopedTimer timer(ctx, AIS_K_FUSED);
+  if (dtype == AIS_BF16)
+    launch_typed<bf16_t>(ctx, need, logits, n_rows, vocab, row_stride, token_ids, valid, inv_temperature, logp_out,
+                         lse_out, sgrad);
+  else
+    launch_typed<float>(ctx, need, logits, n_rows, vocab, row_stride, token_ids, valid, inv_temperature, logp_out,
+                        lse_out, sgrad);
+  return hip_fail(ctx, hipGetLastError());
+}
+
+}  // namespace ais

@@ -233,7 +233,7 @@ __global__ __launch_bounds__(kTileThreads) void row_coeff_kernel(
     const long long* __restrict__ cu_rows, int n_resp, const float* __restrict__ adv,
     const int* __restrict__ count, const ais_diag* __restrict__ diag, ais_params p,
     const int* __restrict__ tile_off, double* __restrict__ partial, float* __restrict__ g_out,
-    float* __restrict__ wtilde_out) {
+    float* __restrict__ wtilde_out, float g_scale) {
   __shared__ double lds_d[kTileThreads];
   const int b = blockIdx.x;
   if (b >= tile_off[n_resp]) return;
@@ -271,7 +271,7 @@ __global__ __launch_bounds__(kTileThreads) void row_coeff_kernel(
         dobj -= (double)p.beta_kl * (1.0 - eq);
       }
       acc -= wgt * obj;
-      g = (float)(wgt * dobj);
+      g = (float)(wgt * dobj * (double)g_scale);
       wt = (float)wtilde;
     }
     g_out[n] = g;
@@ -327,11 +327,11 @@ int launch_row_coeff(ais_ctx* ctx, const float* logp_train, const float* logp_ro
                      const float* logp_ref, const unsigned char* valid, long long n_rows,
                      const long long* cu_rows, int n_resp, const float* adv, const int* count,
                      const ais_diag* diag, const ais_params& p, const int* tile_off, int max_tiles,
-                     double* partial, float* g_out, float* wtilde_out, double* loss_out) {
+                     double* partial, float* g_out, float* wtilde_out, double* loss_out, float g_scale) {
   if (max_tiles > 0)
     row_coeff_kernel<<<max_tiles, kTileThreads, 0, ctx->stream>>>(logp_train, logp_roll, logp_old, logp_ref, valid,
                                                                   n_rows, cu_rows, n_resp, adv, count, diag, p,
-                                                                  tile_off, partial, g_out, wtilde_out);
+                                                                  tile_off, partial, g_out, wtilde_out, g_scale);
   loss_final_kernel<<<1, kTileThreads, 0, ctx->stream>>>(partial, tile_off, n_resp, loss_out);
   return hip_fail(ctx, hipGetLastError());
 }

@@ -117,14 +117,15 @@ __global__ __launch_bounds__(kSweepThreads) void token_logprob_kernel(
 template <typename T, bool VEC, int UNROLL>
 __global__ __launch_bounds__(kSweepThreads) void dlogits_kernel(
     const T* logits, long long row_stride, int vocab, const int* __restrict__ token_ids,
-    const float* __restrict__ g, const float* __restrict__ lse, const float* __restrict__ logp,
-    float inv_temperature, T* dlogits) {
+    const float* __restrict__ g, const unsigned char* __restrict__ valid, const float* __restrict__ lse,
+    const float* __restrict__ logp, float inv_temperature, T* dlogits) {
   constexpr int N = Vec<T>::N;
   const long long row = blockIdx.x;
   const int tid = threadIdx.x;
   const T* zr = logits + row * row_stride;
   T* dr = dlogits + row * row_stride;
-  const float gn = g[row];
+  // g == nullptr: unit coefficient on evaluated rows, i.e. the unscaled direction softmax - onehot
+  const float gn = g != nullptr ? g[row] : ((valid == nullptr || valid[row] != 0) ? 1.f : 0.f);
   const int nvec = VEC ? vocab / N : 0;
 
   if (gn == 0.f) {
@@ -139,7 +140,7 @@ __global__ __launch_bounds__(kSweepThreads) void dlogits_kernel(
 
   const float scale = inv_temperature * kLog2e;
   const float shift = -lse[row] * kLog2e;
-  const float c = gn * inv_temperature;
+  const float c = g != nullptr ? gn * inv_temperature : gn;
   int y = token_ids[row];
   if (y < 0 || y >= vocab) y = -1;               // flagged by the first sweep; no one-hot term
   const int yvec = (VEC && y >= 0 && y < nvec * N) ? y / N : -1;
@@ -201,7 +202,15 @@ bool vec_ok(const void* base, long long row_stride, size_t esize) {
   return (reinterpret_cast<uintptr_t>(base) % 16 == 0) && ((row_stride * (long long)esize) % 16 == 0);
 }
 
-constexpr int kUnroll = 4;
+// 16-byte loads in flight per lane and loop iteration (build-time tunables)
+#ifndef AIS_LOGPROB_UNROLL
+#define AIS_LOGPROB_UNROLL 4
+#endif
+#ifndef AIS_DLOGITS_UNROLL
+#define AIS_DLOGITS_UNROLL 4
+#endif
+constexpr int kUnrollFwd = AIS_LOGPROB_UNROLL;
+constexpr int kUnrollBwd = AIS_DLOGITS_UNROLL;
 
 }  // namespace
 
@@ -214,7 +223,7 @@ int launch_token_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, long
   if (dtype == AIS_BF16) {
     const bf16_t* z = static_cast<const bf16_t*>(logits);
     if (vec_ok(z, row_stride, 2))
-      token_logprob_kernel<bf16_t, true, kUnroll><<<grid, block, 0, ctx->stream>>>(
+      token_logprob_kernel<bf16_t, true, kUnrollFwd><<<grid, block, 0, ctx->stream>>>(
           z, row_stride, vocab, token_ids, valid, inv_temperature, logp_out, lse_out, ctx->status_dev);
     else
       token_logprob_kernel<bf16_t, false, 1><<<grid, block, 0, ctx->stream>>>(
@@ -222,7 +231,7 @@ int launch_token_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, long
   } else {
     const float* z = static_cast<const float*>(logits);
     if (vec_ok(z, row_stride, 4))
-      token_logprob_kernel<float, true, kUnroll><<<grid, block, 0, ctx->stream>>>(
+      token_logprob_kernel<float, true, kUnrollFwd><<<grid, block, 0, ctx->stream>>>(
           z, row_stride, vocab, token_ids, valid, inv_temperature, logp_out, lse_out, ctx->status_dev);
     else
       token_logprob_kernel<float, false, 1><<<grid, block, 0, ctx->stream>>>(
@@ -232,8 +241,8 @@ int launch_token_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, long
 }
 
 int launch_dlogits(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,
-                   long long row_stride, const int* token_ids, const float* g, const float* lse,
-                   const float* logp, float inv_temperature, void* dlogits) {
+                   long long row_stride, const int* token_ids, const float* g, const unsigned char* valid,
+                   const float* lse, const float* logp, float inv_temperature, void* dlogits) {
   if (n_rows == 0) return AIS_OK;
   dim3 grid((unsigned)n_rows), block(kSweepThreads);
   ScopedTimer timer(ctx, AIS_K_DLOGITS);
@@ -241,19 +250,19 @@ int launch_dlogits(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long 
     const bf16_t* z = static_cast<const bf16_t*>(logits);
     bf16_t* dz = static_cast<bf16_t*>(dlogits);
     if (vec_ok(z, row_stride, 2) && vec_ok(dz, row_stride, 2))
-      dlogits_kernel<bf16_t, true, kUnroll><<<grid, block, 0, ctx->stream>>>(z, row_stride, vocab, token_ids, g,
-                                                                            lse, logp, inv_temperature, dz);
+      dlogits_kernel<bf16_t, true, kUnrollBwd><<<grid, block, 0, ctx->stream>>>(z, row_stride, vocab, token_ids, g,
+                                                                            valid, lse, logp, inv_temperature, dz);
     else
-      dlogits_kernel<bf16_t, false, 1><<<grid, block, 0, ctx->stream>>>(z, row_stride, vocab, token_ids, g, lse,
+      dlogits_kernel<bf16_t, false, 1><<<grid, block, 0, ctx->stream>>>(z, row_stride, vocab, token_ids, g, valid, lse,
                                                                        logp, inv_temperature, dz);
   } else {
     const float* z = static_cast<const float*>(logits);
     float* dz = static_cast<float*>(dlogits);
     if (vec_ok(z, row_stride, 4) && vec_ok(dz, row_stride, 4))
-      dlogits_kernel<float, true, kUnroll><<<grid, block, 0, ctx->stream>>>(z, row_stride, vocab, token_ids, g, lse,
+      dlogits_kernel<float, true, kUnrollBwd><<<grid, block, 0, ctx->stream>>>(z, row_stride, vocab, token_ids, g, valid, lse,
                                                                           logp, inv_temperature, dz);
     else
-      dlogits_kernel<float, false, 1><<<grid, block, 0, ctx->stream>>>(z, row_stride, vocab, token_ids, g, lse,
+      dlogits_kernel<float, false, 1><<<grid, block, 0, ctx->stream>>>(z, row_stride, vocab, token_ids, g, valid, lse,
                                                                       logp, inv_temperature, dz);
   }
   return hip_fail(ctx, hipGetLastError());

@@ -173,6 +173,30 @@ def test_stale_old_policy_and_kl(ctx, with_kl):
     assert (rho > 1.2).any() and (rho < 0.8).any()
 
 
+@pytest.mark.parametrize("mode", ["tis", "grpo", "clipped_kl_norm_temp"])
+def test_baseline_modes_full_vocab(ctx, mode):
+    """The paper's comparison configurations on the real row geometry (V = 151,936): token-level truncated IS
+    (alpha forced to 1, Eq. 8), uncorrected GRPO (alpha forced to 0), and the general clipped surrogate of
+    Eq. 19 with a stale old policy, the KL term, normalised advantages and a sampling temperature together."""
+    shape = W.config(2).scaled(len_div=96, seed=91)
+    batch = gen(shape, row_chunk=128)
+    if mode == "tis":
+        P.check(ctx, batch, B.default_params(alpha_override=1.0))
+    elif mode == "grpo":
+        out, ref, d = P.check(ctx, batch, B.default_params(alpha_override=0.0))
+        assert d["alpha"] == 0.0
+    else:
+        p = B.default_params(beta_kl=0.02, adv_mode=1, inv_temperature=1 / 0.9)
+        lp = torch.log_softmax(batch.logits.float() * p.inv_temperature, dim=1)
+        lp = lp.gather(1, batch.token_ids.long().unsqueeze(1)).squeeze(1)
+        g = torch.Generator(device="cuda").manual_seed(5)
+        logp_old = lp + 0.2 * torch.randn(lp.shape, device="cuda", generator=g)
+        rho = torch.exp(lp - logp_old)
+        logp_old = torch.where(((rho - 0.8).abs() < 1e-3) | ((rho - 1.2).abs() < 1e-3), lp, logp_old)
+        logp_ref = lp + 0.3 * torch.randn(lp.shape, device="cuda", generator=g)
+        P.check(ctx, batch, p, logp_old=logp_old, logp_ref=logp_ref)
+
+
 def test_in_place_gradient(ctx):
     shape = W.config(2).scaled(vocab=4104, len_div=32, seed=51)
     batch = gen(shape)
