@@ -89,6 +89,8 @@ int launch_row_coeff(ais_ctx* ctx, const float* logp_train, const float* logp_ro
 int launch_copy(ais_ctx* ctx, void* dst, const void* src, long long bytes);
 int launch_fp8_quantize(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,
                         long long row_stride, unsigned char* codes, long long codes_stride, float* scale_out);
+bool try_fp8_quantize_rows(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,
+                           long long row_stride, unsigned char* codes, long long codes_stride, float* scale_out);
 int launch_fp8_dequantize(ais_ctx* ctx, const unsigned char* codes, long long codes_stride, const float* scale,
                           long long n_rows, int vocab, void* out, ais_dtype dtype, long long out_stride);
 int launch_fp8_rollout_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,

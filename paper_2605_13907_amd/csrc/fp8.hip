@@ -7,25 +7,18 @@
 //
 // gfx950's conversion instructions implement the OCP E4M3 format (round to nearest even); inputs are
 // clamped to +-448 first, so the conversion never sees an overflow.  The arithmetic that decides a code is
-// fp32: s = max|z| / 448 and q = z / s, both correctly rounded divisions.
+// fp32: s = max|z| / 448 and q = z / s, both correctly rounded divisions (q through the per-row divider of
+// fp8_utils.h).  Rows that fit the register file take the single-read kernels of fp8_rows.hip.
 #include "ais_internal.h"
 #include "device_utils.h"
+#include "fp8_utils.h"
+
+#include <type_traits>
 
 namespace ais {
 namespace {
 
 using namespace dev;
-
-typedef float f32x2v __attribute__((ext_vector_type(2)));
-constexpr float kE4M3Max = 448.f;
-
-__device__ __forceinline__ float clamp448(float q) { return __builtin_amdgcn_fmed3f(q, -kE4M3Max, kE4M3Max); }
-
-// two fp32 -> two E4M3 codes in the low 16 bits
-__device__ __forceinline__ uint32_t to_e4m3x2(float a, float b) {
-  return (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(clamp448(a), clamp448(b), 0, false) & 0xffffu;
-}
-__device__ __forceinline__ f32x2v from_e4m3x2(uint32_t w) { return __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false); }
 
 // Row abs-max -> scale, shared by the workgroup through LDS.
 template <typename T, bool VEC>
@@ -48,8 +41,7 @@ __device__ __forceinline__ float row_scale(const T* zr, int vocab, float* lds) {
   if ((tid & 63) == 0) lds[tid >> 6] = amax;
   __syncthreads();
   amax = fmaxf(fmaxf(lds[0], lds[1]), fmaxf(lds[2], lds[3]));
-  const float s = amax / kE4M3Max;
-  return s > 0.f ? s : 1.f;
+  return scale_of(amax);
 }
 
 template <typename T, bool VEC>
@@ -65,26 +57,32 @@ __global__ __launch_bounds__(kSweepThreads) void fp8_quantize_kernel(const T* __
   unsigned char* cr = codes + row * codes_stride;
   const float s = row_scale<T, VEC>(zr, vocab, lds);
   if (tid == 0) scale_out[row] = s;
+  const RowDivider d = make_divider(s);
   const int nvec = VEC ? vocab / N : 0;
-  if (VEC) {
-    const u32x4* zv = reinterpret_cast<const u32x4*>(zr);
-    for (int i = tid; i < nvec; i += kSweepThreads) {
-      float x[N];
-      Vec<T>::unpack(load_stream(zv + i), x);
-      uint32_t w[N / 4];
+  auto encode = [&](auto slow) {
+    constexpr bool SLOW = decltype(slow)::value;
+    if (VEC) {
+      const u32x4* zv = reinterpret_cast<const u32x4*>(zr);
+      for (int i = tid; i < nvec; i += kSweepThreads) {
+        float x[N];
+        Vec<T>::unpack(load_stream(zv + i), x);
+        uint32_t w[N / 4];
 #pragma unroll
-      for (int k = 0; k < N / 4; ++k)
-        w[k] = to_e4m3x2(x[4 * k] / s, x[4 * k + 1] / s) | (to_e4m3x2(x[4 * k + 2] / s, x[4 * k + 3] / s) << 16);
-      if (N == 8) {
-        uint2 o = {w[0], w[N / 4 - 1]};
-        *reinterpret_cast<uint2*>(cr + (long long)i * N) = o;
-      } else {
-        *reinterpret_cast<uint32_t*>(cr + (long long)i * N) = w[0];
+        for (int k = 0; k < N / 4; ++k)
+          w[k] = to_e4m3x2(divide<SLOW>(x[4 * k], d), divide<SLOW>(x[4 * k + 1], d)) |
+                 (to_e4m3x2(divide<SLOW>(x[4 * k + 2], d), divide<SLOW>(x[4 * k + 3], d)) << 16);
+        if (N == 8) {
+          uint2 o = {w[0], w[N / 4 - 1]};
+          *reinterpret_cast<uint2*>(cr + (long long)i * N) = o;
+        } else {
+          *reinterpret_cast<uint32_t*>(cr + (long long)i * N) = w[0];
+        }
       }
     }
-  }
-  for (int v = nvec * N + tid; v < vocab; v += kSweepThreads)
-    cr[v] = (unsigned char)(to_e4m3x2(Vec<T>::load1(zr + v) / s, 0.f) & 0xffu);
+    for (int v = nvec * N + tid; v < vocab; v += kSweepThreads)
+      cr[v] = (unsigned char)(to_e4m3x2(divide<SLOW>(Vec<T>::load1(zr + v), d), 0.f) & 0xffu);
+  };
+  if (d.slow) encode(std::true_type{}); else encode(std::false_type{});
 }
 
 template <typename T, bool VEC>
@@ -143,26 +141,31 @@ __global__ __launch_bounds__(kSweepThreads) void fp8_rollout_logprob_kernel(
   }
   const T* zr = logits + row * row_stride;
   const float s = row_scale<T, VEC>(zr, vocab, lds);
+  const RowDivider d = make_divider(s);
   const int nvec = VEC ? vocab / N : 0;
   MaxSum st{kNegHuge, 0.f};
-  if (VEC) {
-    const u32x4* zv = reinterpret_cast<const u32x4*>(zr);
-    for (int i = tid; i < nvec; i += kSweepThreads) {
-      float x[N];
-      Vec<T>::unpack(load_stream(zv + i), x);
+  auto sweep = [&](auto slow) {
+    constexpr bool SLOW = decltype(slow)::value;
+    if (VEC) {
+      const u32x4* zv = reinterpret_cast<const u32x4*>(zr);
+      for (int i = tid; i < nvec; i += kSweepThreads) {
+        float x[N];
+        Vec<T>::unpack(load_stream(zv + i), x);
 #pragma unroll
-      for (int k = 0; k < N; k += 2) {
-        const f32x2v r = from_e4m3x2(to_e4m3x2(x[k] / s, x[k + 1] / s));
-        x[k] = r[0] * s;
-        x[k + 1] = r[1] * s;
+        for (int k = 0; k < N; k += 2) {
+          const f32x2v r = from_e4m3x2(to_e4m3x2(divide<SLOW>(x[k], d), divide<SLOW>(x[k + 1], d)));
+          x[k] = r[0] * s;
+          x[k + 1] = r[1] * s;
+        }
+        accumulate<N>(x, kLog2e, st);
       }
-      accumulate<N>(x, kLog2e, st);
     }
-  }
-  for (int v = nvec * N + tid; v < vocab; v += kSweepThreads) {
-    float x = from_e4m3x2(to_e4m3x2(Vec<T>::load1(zr + v) / s, 0.f))[0] * s;
-    accumulate<1>(&x, kLog2e, st);
-  }
+    for (int v = nvec * N + tid; v < vocab; v += kSweepThreads) {
+      float x = from_e4m3x2(to_e4m3x2(divide<SLOW>(Vec<T>::load1(zr + v), d), 0.f))[0] * s;
+      accumulate<1>(&x, kLog2e, st);
+    }
+  };
+  if (d.slow) sweep(std::true_type{}); else sweep(std::false_type{});
   st = wave_merge(st);
   if ((tid & 63) == 0) lds_ms[tid >> 6] = st;
   __syncthreads();
@@ -192,6 +195,8 @@ int launch_fp8_quantize(ais_ctx* ctx, const void* logits, ais_dtype dtype, long 
   if (n_rows == 0) return AIS_OK;
   dim3 grid((unsigned)n_rows), block(kSweepThreads);
   ScopedTimer timer(ctx, AIS_K_FP8_QUANT);
+  if (try_fp8_quantize_rows(ctx, logits, dtype, n_rows, vocab, row_stride, codes, codes_stride, scale_out))
+    return hip_fail(ctx, hipGetLastError());      // row held in registers: one read of the logits
   if (dtype == AIS_BF16) {
     const bf16_t* z = static_cast<const bf16_t*>(logits);
     if (aligned(z, row_stride * 2, 16) && aligned(codes, codes_stride, 8))

@@ -121,10 +121,6 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
     __builtin_amdgcn_sched_barrier(0);   // keeps the unpacked values of one vector short-lived
   }
   accumulate<1>(&xt, scale, st);
-  // The row stays in registers in its packed form: the empty asm makes each vector opaque, so that the
-  // unpacked fp32 values of phase 1 are not kept alive for phase 2 (four times the registers).
-#pragma unroll
-  for (int k = 0; k < NV; ++k) asm volatile("" : "+v"(q[k]));
   st = wave_merge(st);
   if ((tid & 63) == 0) lds[tid >> 6] = st;
   __syncthreads();
@@ -151,6 +147,12 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
   __syncthreads();
   const float shift = lds_row[0];
   const float sy = lds_row[1];
+  // The row stays in registers in its packed form: the empty asm, which names the shift as an input, makes
+  // each vector opaque until the reduction is done, so that neither the unpacked fp32 values of phase 1 are
+  // kept alive nor the unpacking of phase 2 is hoisted above the barrier (either costs a multiple of the
+  // registers).
+#pragma unroll
+  for (int k = 0; k < NV; ++k) asm volatile("" : "+v"(q[k]) : "v"(shift));
 
   // ---- phase 2: softmax from the registers (the patched element comes out as 0) ----
 #pragma unroll

@@ -84,3 +84,40 @@ def test_rollout_logprob_matches_generator_recipe():
     zr_torch = W.fp8_rollout_logits(b.logits.float()).numpy()
     codes, s = F.quantize_rows(z)
     assert np.array_equal(F.dequantize_rows(codes, s), zr_torch)
+
+
+def test_reciprocal_division_scheme_is_correctly_rounded():
+    """The arithmetic the GPU kernels use for z / s, replayed on the CPU with exact rationals and fp32
+    roundings: r = RN(1/s); q0 = RN(x r); q1 = RN(q0 + RN(x - q0 s) r); q = RN(q1 + RN(x - q1 s) r).
+    q1 is a faithful quotient, so its residual is exactly representable, and q equals the correctly rounded
+    quotient for divisors whose significand is not all ones (Markstein's theorem).  The single-correction
+    variant is NOT always correct (q0 can be more than one ulp off): this test also shows such a case."""
+    from fractions import Fraction
+
+    def rn(fr):                      # round a rational to the nearest fp32, ties to even
+        f = np.float32(float(fr))    # float(Fraction) is correctly rounded to fp64; then fp64 -> fp32
+        cands = [np.nextafter(f, np.float32(-np.inf)), f, np.nextafter(f, np.float32(np.inf))]
+        best = min(cands, key=lambda c: (abs(Fraction(float(c)) - fr), int(np.float32(c).view(np.uint32)) & 1))
+        return np.float32(best)
+
+    F = lambda v: Fraction(float(v))
+    rng = np.random.default_rng(5)
+    first_residual_inexact = 0
+    cases = [(np.float32(-52187192.0), np.float32(130199.8359375))]       # q0 is 1.03 ulp off here
+    for _ in range(3000):
+        s = np.float32(10.0 ** rng.uniform(-6, 6) * rng.uniform(1, 2))
+        cases.append((np.float32(rng.uniform(-448, 448) * float(s)), s))
+    for x, s in cases:
+        if (s.view(np.uint32) & 0x7FFFFF) == 0x7FFFFF:
+            continue
+        fs, fx = F(s), F(x)
+        r = rn(1 / fs)
+        q0 = rn(fx * F(r))
+        e0 = rn(fx - F(q0) * fs)
+        first_residual_inexact += F(e0) != fx - F(q0) * fs
+        q1 = rn(F(q0) + F(e0) * F(r))
+        e1 = rn(fx - F(q1) * fs)
+        assert F(e1) == fx - F(q1) * fs, (x, s)                  # residual of the faithful quotient: exact
+        q = rn(F(q1) + F(e1) * F(r))
+        assert q == rn(fx / fs), (x, s)
+    assert first_residual_inexact >= 1

@@ -72,6 +72,51 @@ def test_random_rows(ctx, dtype, vocab):
     assert np.abs(lp.double().cpu().numpy() - ref).max() <= LOGP_ATOL
 
 
+def all_ones_scale_absmax():
+    """An fp32 abs-max whose scale RN(amax / 448) has an all-ones significand (the divisor the reciprocal
+    scheme must hand to the true division), found by search on the CPU."""
+    for e in range(-3, 4):
+        target = np.float32((2.0 - 2.0 ** -23) * 2.0 ** e)
+        a = np.float32(target * np.float32(448.0))
+        for _ in range(64):
+            s = np.float32(a / np.float32(448.0))
+            if (s.view(np.uint32) & 0x7FFFFF) == 0x7FFFFF:
+                return float(a)
+            a = np.nextafter(a, np.float32(np.inf) if s < target else np.float32(-np.inf))
+    return None
+
+
+def test_division_by_the_row_scale_is_correctly_rounded(ctx):
+    """Codes depend on RN(z / s).  The kernels divide through a per-row reciprocal with an fma correction; rows
+    whose scale is unsuitable for that (all-ones significand, extreme exponents) take the true division.
+    Both routes must give the oracle's codes bit for bit, over many scales and dense values."""
+    rng = np.random.default_rng(11)
+    rows = []
+    amaxes = list(10.0 ** rng.uniform(-30, 30, size=40)) + [448.0, 1.0, 3.0, 7.0 * 2 ** 20, 1e-38, 3e38]
+    special = all_ones_scale_absmax()
+    if special is not None:
+        amaxes += [special, special * 4]
+    V = 8192
+    for amax in amaxes:
+        a = np.float32(amax)
+        x = (rng.uniform(-1, 1, size=V) * a).astype(np.float32)
+        x[0] = a
+        x[1] = -a
+        # values at and next to rounding boundaries of the quotient: (k + 1/2) steps of the E4M3 grid times s
+        s = np.float32(a / np.float32(448.0))
+        grid = np.array([(k + 0.5) * 2.0 ** e for e in range(-9, 5) for k in range(8, 16)], dtype=np.float64)
+        edge = (grid[:400] * np.float64(s)).astype(np.float32)
+        x[2:2 + edge.size] = edge
+        x[2 + edge.size:2 + 2 * edge.size] = np.nextafter(edge, np.float32(np.inf))
+        x[2 + 2 * edge.size:2 + 3 * edge.size] = np.nextafter(edge, np.float32(-np.inf))
+        rows.append(np.clip(x, -a, a))
+    z = torch.from_numpy(np.stack(rows)).cuda()
+    check_quant(ctx, z)
+    if special is not None:
+        s = np.float32(np.float32(special) / np.float32(448.0))
+        assert (s.view(np.uint32) & 0x7FFFFF) == 0x7FFFFF
+
+
 def test_pitch_and_misalignment(ctx):
     z = torch.randn(9, 3016, device="cuda").mul_(3).to(torch.bfloat16)
     check_quant(ctx, z[:, :3003])                         # row pitch > vocab, vector body + scalar tail
