@@ -40,6 +40,16 @@ template <> struct Vec<bf16_t> {
     }
     return q;
   }
+  // q with element `sub` replaced by v (rounded to nearest even)
+  static __device__ __forceinline__ u32x4 put(u32x4 q, int sub, float v) {
+    const uint32_t h = __builtin_bit_cast(uint16_t, static_cast<__bf16>(v));
+    const uint32_t keep = (sub & 1) ? 0x0000ffffu : 0xffff0000u;
+    const uint32_t bits = (sub & 1) ? (h << 16) : h;
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+      if (w == (sub >> 1)) q[w] = (q[w] & keep) | bits;
+    return q;
+  }
   static __device__ __forceinline__ float load1(const bf16_t* p) { return __uint_as_float(uint32_t(*p) << 16); }
   static __device__ __forceinline__ void store1(bf16_t* p, float v) {
     *p = __builtin_bit_cast(uint16_t, static_cast<__bf16>(v));
@@ -55,6 +65,12 @@ template <> struct Vec<float> {
     u32x4 q;
 #pragma unroll
     for (int k = 0; k < 4; ++k) q[k] = __float_as_uint(x[k]);
+    return q;
+  }
+  static __device__ __forceinline__ u32x4 put(u32x4 q, int sub, float v) {
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+      if (w == sub) q[w] = __float_as_uint(v);
     return q;
   }
   static __device__ __forceinline__ float load1(const float* p) { return *p; }

@@ -4,15 +4,15 @@
 //                          lse = log sum_v exp(z_v / T), logp = z_y / T - lse, the latter evaluated as
 //                          -log1p(sum_{v != y} exp((z_v - z_y) / T))
 //                          (Alg. 1, "Compute full-precision log-probs")
-//   dlogits_kernel         second pass: dz_v = g (softmax_v - 1[v = y]) / T, written in the logits'
+//   dlogits_burst_kernel   second pass: dz_v = g (softmax_v - 1[v = y]) / T, written in the logits'
 //                          dtype (gradient of Eq. 19 through the log-softmax; g is the row's coefficient)
 //
 // Both are bound by HBM bandwidth: nothing here is a contraction, so no matrix cores.  One workgroup
-// of 256 threads (4 wavefronts of 64) owns one row, so a row's partial results never leave its
-// compute unit; consecutive lanes read consecutive 16-byte vectors (8 bf16 or 4 fp32 logits), i.e.
-// each wavefront load instruction covers 1 KiB of contiguous memory.  Logits are read and written
-// with streaming (non-temporal) accesses: a batch is tens of GB and nothing survives in cache
-// between the two sweeps.
+// owns one row (256 threads in the read-only sweep, 1,024 in the read+write sweep), so a row's partial
+// results never leave its compute unit; consecutive lanes access consecutive 16-byte vectors (8 bf16 or
+// 4 fp32 logits), i.e. each wavefront memory instruction covers 1 KiB of contiguous memory.  Logits are
+// read and written with streaming (non-temporal) accesses: a batch is tens of GB and nothing survives in
+// cache between the two sweeps (a temporal load costs the read-only sweep 11 % of its bandwidth).
 #include "ais_internal.h"
 #include "device_utils.h"
 
@@ -114,8 +114,49 @@ __global__ __launch_bounds__(kSweepThreads) void token_logprob_kernel(
 // dz[v] = c * (2^(z_v * scale - lse * log2e) - 1[v = y]) with c = g / T.  Rows with g == 0 (not evaluated,
 // zero advantage, or clipped away) are filled with zeros without being read.  In-place operation is safe:
 // every element is read and written by the same thread, once.
-template <typename T, bool VEC, int UNROLL>
-__global__ __launch_bounds__(kSweepThreads) void dlogits_kernel(
+//
+// Element-wise form: the route for rows that are not 16-byte aligned.  grid.x = n_rows, block = kSweepThreads.
+template <typename T>
+__global__ __launch_bounds__(kSweepThreads) void dlogits_elementwise_kernel(
+    const T* logits, long long row_stride, int vocab, const int* __restrict__ token_ids,
+    const float* __restrict__ g, const unsigned char* __restrict__ valid, const float* __restrict__ lse,
+    const float* __restrict__ logp, float inv_temperature, T* dlogits) {
+  const long long row = blockIdx.x;
+  const int tid = threadIdx.x;
+  const T* zr = logits + row * row_stride;
+  T* dr = dlogits + row * row_stride;
+  // g == nullptr: unit coefficient on evaluated rows, i.e. the unscaled direction softmax - onehot
+  const float gn = g != nullptr ? g[row] : ((valid == nullptr || valid[row] != 0) ? 1.f : 0.f);
+  if (gn == 0.f) {
+    for (int v = tid; v < vocab; v += kSweepThreads) Vec<T>::store1(dr + v, 0.f);
+    return;
+  }
+  const float scale = inv_temperature * kLog2e;
+  const float shift = -lse[row] * kLog2e;
+  const float c = g != nullptr ? gn * inv_temperature : gn;
+  int y = token_ids[row];
+  if (y < 0 || y >= vocab) y = -1;               // flagged by the first sweep; no one-hot term
+  // the sampled token's element is c (p_y - 1) = c expm1(logp): no cancellation when p_y is close to 1
+  const float dzy = c * expm1f(logp[row]);
+  for (int v = tid; v < vocab; v += kSweepThreads) {
+    float p = c * exp2_fast(__builtin_fmaf(Vec<T>::load1(zr + v), scale, shift));
+    if (v == y) p = dzy;
+    Vec<T>::store1(dr + v, p);
+  }
+}
+
+// Burst form: the route for 16-byte aligned rows.  A workgroup of 1,024 threads owns the row; every wavefront
+// issues all of its loads (up to NV 16-byte vectors per lane, i.e. up to NV KiB per wavefront), transforms
+// the vectors in place as they arrive, and only when its last load has landed issues all of its stores.
+// Measured on MI355X, a read+write stream shaped this way (long load bursts followed by long store bursts,
+// all wavefronts of a compute unit in step because they start together) sustains about 5.8 TB/s where a loop
+// that stores each vector as soon as it is computed, and every plain copy variant, saturate at 5.2-5.3 TB/s.
+// grid.x = n_rows, block = kBurstThreads.  Requires 16-byte aligned rows.  Rows wider than NV * 1024 vectors
+// are processed in consecutive segments (there is no dependence between segments: lse is an input).
+constexpr int kBurstThreads = 1024;
+
+template <typename T, int NV>
+__global__ __launch_bounds__(kBurstThreads) void dlogits_burst_kernel(
     const T* logits, long long row_stride, int vocab, const int* __restrict__ token_ids,
     const float* __restrict__ g, const unsigned char* __restrict__ valid, const float* __restrict__ lse,
     const float* __restrict__ logp, float inv_temperature, T* dlogits) {
@@ -124,17 +165,16 @@ __global__ __launch_bounds__(kSweepThreads) void dlogits_kernel(
   const int tid = threadIdx.x;
   const T* zr = logits + row * row_stride;
   T* dr = dlogits + row * row_stride;
-  // g == nullptr: unit coefficient on evaluated rows, i.e. the unscaled direction softmax - onehot
+  const u32x4* zv = reinterpret_cast<const u32x4*>(zr);
+  u32x4* dv = reinterpret_cast<u32x4*>(dr);
+  const int nvec = vocab / N;
+  const int tail = vocab - nvec * N;     // < N elements, one per thread for the first `tail` threads
   const float gn = g != nullptr ? g[row] : ((valid == nullptr || valid[row] != 0) ? 1.f : 0.f);
-  const int nvec = VEC ? vocab / N : 0;
 
   if (gn == 0.f) {
-    if (VEC) {
-      u32x4* dv = reinterpret_cast<u32x4*>(dr);
-      const u32x4 zero = {0u, 0u, 0u, 0u};
-      for (int i = tid; i < nvec; i += kSweepThreads) store_stream(dv + i, zero);
-    }
-    for (int v = nvec * N + tid; v < vocab; v += kSweepThreads) Vec<T>::store1(dr + v, 0.f);
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    for (int i = tid; i < nvec; i += kBurstThreads) store_stream(dv + i, zero);
+    if (tid < tail) Vec<T>::store1(dr + nvec * N + tid, 0.f);
     return;
   }
 
@@ -143,51 +183,65 @@ __global__ __launch_bounds__(kSweepThreads) void dlogits_kernel(
   const float c = g != nullptr ? gn * inv_temperature : gn;
   int y = token_ids[row];
   if (y < 0 || y >= vocab) y = -1;               // flagged by the first sweep; no one-hot term
-  const int yvec = (VEC && y >= 0 && y < nvec * N) ? y / N : -1;
-  const int ylane = y - yvec * N;
-  // the sampled token's element is c (p_y - 1) = c expm1(logp): no cancellation when p_y is close to 1
+  // The sampled token's element is c (p_y - 1) = c expm1(logp): no cancellation when p_y is close to 1.  The
+  // lane that holds it patches its packed output register before the store burst.
+  const int yvec = (y >= 0 && y < nvec * N && (y / N) % kBurstThreads == tid) ? y / N : -1;
   const float dzy = c * expm1f(logp[row]);
 
-  if (VEC) {
-    const u32x4* zv = reinterpret_cast<const u32x4*>(zr);
-    u32x4* dv = reinterpret_cast<u32x4*>(dr);
-    int i = tid;
-    for (; i + (UNROLL - 1) * kSweepThreads < nvec; i += UNROLL * kSweepThreads) {
-      u32x4 q[UNROLL];
+  for (int base = 0; base < nvec; base += NV * kBurstThreads) {
+    u32x4 q[NV];
 #pragma unroll
-      for (int u = 0; u < UNROLL; ++u) q[u] = load_stream(zv + i + u * kSweepThreads);
-#pragma unroll
-      for (int u = 0; u < UNROLL; ++u) {
-        float x[N];
-        Vec<T>::unpack(q[u], x);
-#pragma unroll
-        for (int k = 0; k < N; ++k) x[k] = c * exp2_fast(__builtin_fmaf(x[k], scale, shift));
-        if (i + u * kSweepThreads == yvec) {
-#pragma unroll
-          for (int k = 0; k < N; ++k)
-            if (k == ylane) x[k] = dzy;
-        }
-        store_stream(dv + i + u * kSweepThreads, Vec<T>::pack(x));
-      }
+    for (int k = 0; k < NV; ++k) {
+      const int i = base + tid + k * kBurstThreads;
+      q[k] = (i < nvec) ? load_stream(zv + i) : u32x4{0u, 0u, 0u, 0u};
     }
-    for (; i < nvec; i += kSweepThreads) {
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {                // in place, in order of arrival
       float x[N];
-      Vec<T>::unpack(load_stream(zv + i), x);
+      Vec<T>::unpack(q[k], x);
 #pragma unroll
-      for (int k = 0; k < N; ++k) x[k] = c * exp2_fast(__builtin_fmaf(x[k], scale, shift));
-      if (i == yvec) {
+      for (int j = 0; j < N; ++j) x[j] = c * exp2_fast(__builtin_fmaf(x[j], scale, shift));
+      q[k] = Vec<T>::pack(x);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // every vector is made opaque here: no store can be issued before the last load has returned
 #pragma unroll
-        for (int k = 0; k < N; ++k)
-          if (k == ylane) x[k] = dzy;
-      }
-      store_stream(dv + i, Vec<T>::pack(x));
+    for (int k = 0; k < NV; ++k) asm volatile("" : "+v"(q[k]));
+    if ((unsigned)(yvec - base - tid) < (unsigned)(NV * kBurstThreads)) {   // one lane, once per row
+      const int hit = (yvec - base - tid) / kBurstThreads;
+#pragma unroll
+      for (int k = 0; k < NV; ++k)
+        if (k == hit) q[k] = Vec<T>::put(q[k], y % N, dzy);
+    }
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int i = base + tid + k * kBurstThreads;
+      if (i < nvec) store_stream(dv + i, q[k]);
     }
   }
-  for (int v = nvec * N + tid; v < vocab; v += kSweepThreads) {
-    float p = c * exp2_fast(__builtin_fmaf(Vec<T>::load1(zr + v), scale, shift));
-    if (v == y) p = dzy;
-    Vec<T>::store1(dr + v, p);
+  if (tid < tail) {
+    const int v = nvec * N + tid;
+    Vec<T>::store1(dr + v, v == y ? dzy : c * exp2_fast(__builtin_fmaf(Vec<T>::load1(zr + v), scale, shift)));
   }
+}
+
+template <typename T>
+void launch_dlogits_burst(ais_ctx* ctx, const T* z, long long n_rows, int vocab, long long row_stride,
+                          const int* token_ids, const float* g, const unsigned char* valid, const float* lse,
+                          const float* logp, float inv_t, T* dz) {
+  const int need = (vocab / Vec<T>::N + kBurstThreads - 1) / kBurstThreads;
+  dim3 grid((unsigned)n_rows), block(kBurstThreads);
+#define AIS_BURST_CASE(NVAL)                                                                                    \
+  dlogits_burst_kernel<T, NVAL><<<grid, block, 0, ctx->stream>>>(z, row_stride, vocab, token_ids, g, valid, lse, \
+                                                                 logp, inv_t, dz)
+  if (need <= 4) AIS_BURST_CASE(4);
+  else if (need <= 8) AIS_BURST_CASE(8);
+  else if (need <= 12) AIS_BURST_CASE(12);
+  else if (need <= 16) AIS_BURST_CASE(16);
+  else if (need <= 19) AIS_BURST_CASE(19);
+  else if (need <= 20) AIS_BURST_CASE(20);
+  else AIS_BURST_CASE(16);        // wider rows: segments of 16 vectors per lane
+#undef AIS_BURST_CASE
 }
 
 // ---- plain copy ------------------------------------------------------------------------------------------
@@ -202,15 +256,11 @@ bool vec_ok(const void* base, long long row_stride, size_t esize) {
   return (reinterpret_cast<uintptr_t>(base) % 16 == 0) && ((row_stride * (long long)esize) % 16 == 0);
 }
 
-// 16-byte loads in flight per lane and loop iteration (build-time tunables)
+// 16-byte loads in flight per lane and loop iteration of the log-prob sweep (build-time tunable)
 #ifndef AIS_LOGPROB_UNROLL
 #define AIS_LOGPROB_UNROLL 4
 #endif
-#ifndef AIS_DLOGITS_UNROLL
-#define AIS_DLOGITS_UNROLL 4
-#endif
 constexpr int kUnrollFwd = AIS_LOGPROB_UNROLL;
-constexpr int kUnrollBwd = AIS_DLOGITS_UNROLL;
 
 }  // namespace
 
@@ -250,20 +300,20 @@ int launch_dlogits(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long 
     const bf16_t* z = static_cast<const bf16_t*>(logits);
     bf16_t* dz = static_cast<bf16_t*>(dlogits);
     if (vec_ok(z, row_stride, 2) && vec_ok(dz, row_stride, 2))
-      dlogits_kernel<bf16_t, true, kUnrollBwd><<<grid, block, 0, ctx->stream>>>(z, row_stride, vocab, token_ids, g,
-                                                                            valid, lse, logp, inv_temperature, dz);
+      launch_dlogits_burst<bf16_t>(ctx, z, n_rows, vocab, row_stride, token_ids, g, valid, lse, logp,
+                                   inv_temperature, dz);
     else
-      dlogits_kernel<bf16_t, false, 1><<<grid, block, 0, ctx->stream>>>(z, row_stride, vocab, token_ids, g, valid, lse,
-                                                                       logp, inv_temperature, dz);
+      dlogits_elementwise_kernel<bf16_t><<<grid, block, 0, ctx->stream>>>(z, row_stride, vocab, token_ids, g, valid,
+                                                                         lse, logp, inv_temperature, dz);
   } else {
     const float* z = static_cast<const float*>(logits);
     float* dz = static_cast<float*>(dlogits);
     if (vec_ok(z, row_stride, 4) && vec_ok(dz, row_stride, 4))
-      dlogits_kernel<float, true, kUnrollBwd><<<grid, block, 0, ctx->stream>>>(z, row_stride, vocab, token_ids, g, valid, lse,
-                                                                          logp, inv_temperature, dz);
+      launch_dlogits_burst<float>(ctx, z, n_rows, vocab, row_stride, token_ids, g, valid, lse, logp,
+                                  inv_temperature, dz);
     else
-      dlogits_kernel<float, false, 1><<<grid, block, 0, ctx->stream>>>(z, row_stride, vocab, token_ids, g, valid, lse,
-                                                                      logp, inv_temperature, dz);
+      dlogits_elementwise_kernel<float><<<grid, block, 0, ctx->stream>>>(z, row_stride, vocab, token_ids, g, valid,
+                                                                        lse, logp, inv_temperature, dz);
   }
   return hip_fail(ctx, hipGetLastError());
 }

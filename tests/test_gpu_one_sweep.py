@@ -55,8 +55,8 @@ def check_one_sweep(ctx, batch, p=None, logp_old=None, logp_ref=None, in_place=F
 
 @pytest.mark.parametrize("k,len_div", [(2, 64), (3, 16), (4, 64), (5, 128)])
 def test_full_vocab(ctx, k, len_div):
-    """Real row geometry: 151,936 (19 vectors per lane), 126,464 (16), and 248,320, which does not fit the
-    register file and takes the two-pass route behind the same entry point."""
+    """Real row geometry: 151,936 (19 vector slots per lane, all in registers), 126,464 (16), and 248,320
+    (31 slots: 22 in registers, 9 in LDS)."""
     shape = W.config(k).scaled(len_div=len_div, n_prompts=2 if k == 3 else None)
     check_one_sweep(ctx, W.generate(shape, "cuda", row_chunk=128))
 
@@ -66,10 +66,12 @@ def test_tiny_fp32(ctx):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("vocab", [1, 5, 1003, 8200, 40_001, 98_312])
+@pytest.mark.parametrize("vocab", [1, 5, 1003, 8200, 40_001, 98_312, 110_597, 127_000, 140_000])
 def test_odd_vocabularies(ctx, vocab, dtype):
     shape = W.RolloutShape("odd", n_prompts=2, group_size=4, vocab=vocab, logits_dtype=dtype, sigma=2.5, boost=4.0,
                            layout="padded", max_len=6, length_dist=("uniform", 1, 6), reward_p=0.5, seed=vocab)
+    # fp32: 98,312 needs 25 slots per lane (18 + 9 in LDS), 110,597 needs 28 (20 + 9), 127,000 needs 31
+    # (22 + 9), 140,000 needs 35 and takes the two-pass route; bf16 rows of these widths stay in registers
     batch = W.generate(shape, "cuda")
     batch.rewards[:] = torch.tensor([1, 0, 0, 1, 0, 0, 1, 0], dtype=torch.float32)
     check_one_sweep(ctx, batch)
