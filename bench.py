@@ -23,15 +23,17 @@ HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E, vendor figure
 
 def measured_traffic(kernel: str, workload: int):
     """HBM bytes per launch from the hardware-counter summaries under profiles/, or None when there is no
-    summary for this kernel and workload or the kernel source has changed since the counters were taken."""
+    summary for this kernel and workload or the kernel sources have changed since the counters were taken."""
     import glob
     import hashlib
     import re
-    src = os.path.join(ROOT, "paper_2605_13907_amd", "csrc", "sweeps.hip")
-    sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    csrc = os.path.join(ROOT, "paper_2605_13907_amd", "csrc")
     for path in glob.glob(os.path.join(ROOT, "profiles", "pmc_hbm_traffic_*.txt")):
         text = open(path).read()
-        if f"sweeps.hip sha256={sha}" not in text:
+        stamped = re.findall(r"^(\S+) sha256=([0-9a-f]{64})$", text, flags=re.M)
+        if not stamped:
+            continue
+        if any(hashlib.sha256(open(os.path.join(csrc, f), "rb").read()).hexdigest() != h for f, h in stamped):
             continue
         m = re.search(rf"^{kernel} workload={workload} traffic_bytes_per_launch=(\d+)", text, flags=re.M)
         if m:
@@ -78,7 +80,7 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = Qwen3-8B-shaped, V = 151,936)")
-    ap.add_argument("--cpu-rows", type=int, default=6144, help="rows of the batch the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of the batch the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--in-place", action="store_true", help="write the gradient over the logits")
     ap.add_argument("--extras", action="store_true",
                     help="also time the FP8 rollout-perturbation kernels on the same batch (reported under next_rows)")
@@ -172,9 +174,9 @@ def main():
                    "responses": shape.n_resp, "group_size": shape.group_size, "logits": shape.logits_dtype,
                    "layout": shape.layout, "in_place": bool(args.in_place), "mode": args.mode,
                    "stale_old_policy": bool(args.stale_old)},
-        "roofline": {"bound": "hbm", "kernel": "dlogits_kernel", "achieved": bwd_gbps, "peak": HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "dlogits_burst_kernel", "achieved": bwd_gbps, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": bwd_gbps / HBM_PEAK_GBPS,
-                     "traffic": measured_traffic("dlogits_kernel", args.config),
+                     "traffic": measured_traffic("dlogits_burst_kernel", args.config),
                      "avg_ms": ms_bwd / n_bwd, "bytes_per_launch": bwd_bytes},
         "kernels": {"token_logprob": {"avg_ms": ms_fwd / n_fwd, "GB/s": fwd_gbps, "frac": fwd_gbps / HBM_PEAK_GBPS},
                     "dlogits": {"avg_ms": ms_bwd / n_bwd, "GB/s": bwd_gbps, "frac": bwd_gbps / HBM_PEAK_GBPS},
