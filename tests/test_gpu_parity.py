@@ -1,5 +1,7 @@
 """GPU parity: the HIP path (through the C ABI) against the CPU fp64 oracle on the same seeded inputs.
 Tolerances are defined in tests/parity.py."""
+from dataclasses import replace as dataclasses_replace
+
 import numpy as np
 import pytest
 import torch
@@ -128,6 +130,30 @@ def test_single_row_and_empty(ctx):
     torch.cuda.synchronize()
     assert ctx.read_diag(diag)["n_valid"] == 0 and float(loss.item()) == 0.0
     assert adv.tolist() == [0.5, -0.5] and count.tolist() == [0, 0]
+
+
+def test_many_short_responses(ctx):
+    """More responses than threads in the planning workgroup (each thread scans a chunk of responses), many of
+    them one or two rows long, several empty, plus a few longer than one reduction tile."""
+    rng = np.random.default_rng(3)
+    G, n_prompts, V = 4, 300, 264
+    B_ = G * n_prompts
+    lens = rng.integers(0, 4, size=B_)
+    lens[rng.integers(0, B_, size=40)] = 0
+    lens[[7, 500, 1199]] = [1500, 2300, 1025]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    R = int(cu[-1])
+    shape = W.RolloutShape("short", n_prompts=n_prompts, group_size=G, vocab=V, logits_dtype="bf16", sigma=3.0,
+                           boost=0.0, layout="packed", max_len=1, length_dist=("fixed",), reward_p=0.5, seed=12)
+    base = gen(dataclasses_replace(shape, n_prompts=1, group_size=1, max_len=R))    # R rows of logits / tokens
+    gcpu = torch.Generator().manual_seed(4)
+    batch = W.RolloutBatch(shape=shape, logits=base.logits, token_ids=base.token_ids,
+                           valid=(torch.rand(R, generator=gcpu) < 0.9).to(torch.uint8).cuda(),
+                           cu_rows=torch.from_numpy(cu).cuda(), logp_roll=base.logp_roll,
+                           rewards=(torch.rand(B_, generator=gcpu) < 0.5).float().cuda(),
+                           lengths=torch.from_numpy(lens))
+    out, ref, d = P.check(ctx, batch)
+    assert d["n_valid"] == int(batch.valid.sum().item()) and (out["count"] == 0).sum().item() >= 40
 
 
 def test_all_ratios_truncated(ctx):
