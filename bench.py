@@ -176,7 +176,7 @@ def main():
         "metric": "fused_logprob_ais_grad_tokens_per_s", "value": N / (ms_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if shape.logits_dtype == "f32" else "f32 (bf16 storage)", "data": "synthetic",
+        "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config {args.config}: {shape.name}", "vocab": V, "rows": R, "valid_rows": N,
                    "responses": shape.n_resp, "group_size": shape.group_size, "logits": shape.logits_dtype,
                    "layout": shape.layout, "in_place": bool(args.in_place), "mode": args.mode,
