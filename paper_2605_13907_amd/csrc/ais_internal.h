@@ -29,7 +29,7 @@ struct DiagPartial {
 
 // Byte offsets of the regions of the context workspace for a call with (n_rows, n_resp).
 struct WorkspaceLayout {
-  size_t tile_off;   // int [n_resp + 1]   first tile of each response
+  size_t tile_off;   // int [n_resp + 2]   first tile of each response, total, and the ticket counter
   size_t partial;    // DiagPartial [max_tiles]  (reused as double [max_tiles] by the loss)
   size_t g;          // float [n_rows]     per-row gradient coefficient
   size_t total;
@@ -79,12 +79,12 @@ int launch_fused_logprob_softmax(ais_ctx* ctx, const void* logits, ais_dtype dty
 int launch_plan(ais_ctx* ctx, const long long* cu_rows, int n_resp, long long n_rows, int* tile_off, int max_tiles);
 int launch_diagnostics(ais_ctx* ctx, const float* logp_train, const float* logp_roll, const unsigned char* valid,
                        long long n_rows, const long long* cu_rows, int n_resp, int group_size,
-                       const float* rewards, const ais_params& p, const int* tile_off, int max_tiles,
+                       const float* rewards, const ais_params& p, int* tile_off, int max_tiles,
                        DiagPartial* partial, float* adv_out, int* count_out, ais_diag* diag_out);
 int launch_row_coeff(ais_ctx* ctx, const float* logp_train, const float* logp_roll, const float* logp_old,
                      const float* logp_ref, const unsigned char* valid, long long n_rows,
                      const long long* cu_rows, int n_resp, const float* adv, const int* count,
-                     const ais_diag* diag, const ais_params& p, const int* tile_off, int max_tiles,
+                     const ais_diag* diag, const ais_params& p, int* tile_off, int max_tiles,
                      double* partial, float* g_out, float* wtilde_out, double* loss_out, float g_scale);
 int launch_copy(ais_ctx* ctx, void* dst, const void* src, long long bytes);
 int launch_fp8_quantize(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,

@@ -2,8 +2,8 @@
 //
 // The batch is a set of variable-length segments (responses) of rows, some rows masked out.  A small
 // plan kernel cuts every response into tiles of kTileRows rows; level 1 reduces one tile per workgroup
-// through LDS to a partial; level 2 (one workgroup) folds the partials of each response in order, forms
-// the group-relative advantages (Eq. 3) and the batch moments, and evaluates the three diagnostics and
+// through LDS to a partial; level 2, run by whichever workgroup of the same launch finishes last, folds the
+// partials of each response in order, forms the group-relative advantages (Eq. 3) and the batch moments, and evaluates the three diagnostics and
 // the mixing coefficient (Eq. 12-17).  Everything is accumulated in fp64 in a fixed order (no floating
 // point atomics), so results are bit-reproducible from run to run.  These kernels move a few bytes per
 // row (about a megabyte per batch) and are latency-bound; the time of the path is in the two sweeps.
@@ -27,9 +27,11 @@ __device__ __forceinline__ void response_rows(const long long* cu_rows, int i, l
 // One workgroup.  Each thread owns a contiguous chunk of responses; thread 0 scans the 256 chunk totals.
 __global__ __launch_bounds__(kTileThreads) void plan_kernel(const long long* __restrict__ cu_rows, int n_resp,
                                                             long long n_rows, int* __restrict__ tile_off,
-                                                            int max_tiles, int* __restrict__ status) {
+                                                            int max_tiles, int* __restrict__ status,
+                                                            int* __restrict__ ticket) {
   __shared__ long long chunk_sum[kTileThreads];
   const int tid = threadIdx.x;
+  if (tid == 0) *ticket = 0;         // counts the finished workgroups of the reduction kernel that follows
   const int per = (n_resp + kTileThreads - 1) / kTileThreads;
   const int i0 = min(n_resp, tid * per), i1 = min(n_resp, i0 + per);
   long long sum = 0;
@@ -90,54 +92,31 @@ __device__ __forceinline__ V block_sum(V v, V* lds) {
   return r;
 }
 
-// ---- level 1: one tile of one response -> DiagPartial -----------------------------------------------------
-__global__ __launch_bounds__(kTileThreads) void diag_partial_kernel(
-    const float* __restrict__ logp_train, const float* __restrict__ logp_roll,
-    const unsigned char* __restrict__ valid, long long n_rows, const long long* __restrict__ cu_rows, int n_resp,
-    const int* __restrict__ tile_off, float C, DiagPartial* __restrict__ partial) {
-  __shared__ double lds_d[kTileThreads];
-  __shared__ long long lds_i[kTileThreads];
-  const int b = blockIdx.x;
-  if (b >= tile_off[n_resp]) return;                 // uniform for the workgroup
-  const int i = find_response(tile_off, n_resp, b);
-  long long lo, hi;
-  response_rows(cu_rows, i, n_rows, lo, hi);
-  const long long r0 = lo + (long long)(b - tile_off[i]) * kTileRows;
-  const long long r1 = min(hi, r0 + kTileRows);
-  const double lnC = log((double)C);
-  double su = 0, su2 = 0, sabs = 0, sd = 0, sdp = 0;
-  long long cnt = 0, nclip = 0;
-  for (long long n = r0 + threadIdx.x; n < r1; n += kTileThreads) {
-    if (valid != nullptr && valid[n] == 0) continue;
-    const double lt = (double)logp_train[n], lr = (double)logp_roll[n];
-    const double d = lt - lr;                                            // log rho (Alg. 1, sampler-trainer ratio)
-    const double u = exp(fmin(d, lnC)) - 1.0;                            // w_bar - 1, w_bar = min(rho, C) (Eq. 10)
-    su += u;
-    su2 += u * u;
-    sabs += fabs(d);
-    sd += d;
-    sdp += fabs(exp(lt) - exp(lr));
-    cnt += 1;
-    nclip += (d > lnC) ? 1 : 0;
+// True in exactly one workgroup of the grid: the one that finishes last.  Every workgroup calls this once,
+// after its own results are written; the caller's writes are made visible device-wide before the ticket is
+// taken, and the last workgroup sees all of them.  Level 2 of each reduction runs in that workgroup, which
+// saves a kernel launch per reduction; the order in which level 2 folds the partials does not depend on which
+// workgroup happens to be last, so results stay bit-reproducible.
+__device__ __forceinline__ bool last_workgroup(int* ticket) {
+  __shared__ int s_last;
+  __syncthreads();                           // this workgroup's result has been written by thread 0
+  if (threadIdx.x == 0) {
+    __threadfence();
+    s_last = (atomicAdd(ticket, 1) == (int)gridDim.x - 1);
   }
-  DiagPartial p;
-  p.su = block_sum(su, lds_d);
-  p.su2 = block_sum(su2, lds_d);
-  p.sabs = block_sum(sabs, lds_d);
-  p.sd = block_sum(sd, lds_d);
-  p.sdp = block_sum(sdp, lds_d);
-  p.cnt = block_sum(cnt, lds_i);
-  p.nclip = block_sum(nclip, lds_i);
-  if (threadIdx.x == 0) partial[b] = p;
+  __syncthreads();
+  const bool last = s_last != 0;
+  if (last) __threadfence();
+  return last;
 }
 
 // ---- level 2: responses -> advantages, batch moments, diagnostics, alpha --------------------------------------
-__global__ __launch_bounds__(kTileThreads) void diag_final_kernel(
-    const DiagPartial* __restrict__ partial, const int* __restrict__ tile_off, int n_resp, int group_size,
-    const float* __restrict__ rewards, ais_params p, float* __restrict__ adv_out, int* __restrict__ count_out,
-    ais_diag* __restrict__ diag_out, const int* __restrict__ status) {
-  __shared__ double lds_d[kTileThreads];
-  __shared__ long long lds_i[kTileThreads];
+// Runs in the last workgroup of diag_reduce_kernel.  `partial` is volatile: it was written by other
+// workgroups of the same launch and must be read from memory, not from a cache line or register of this one.
+__device__ void diag_final(const volatile DiagPartial* partial, const int* __restrict__ tile_off, int n_resp,
+                           int group_size, const float* __restrict__ rewards, const ais_params& p,
+                           float* __restrict__ adv_out, int* __restrict__ count_out, ais_diag* __restrict__ diag_out,
+                           const int* __restrict__ status, double* lds_d, long long* lds_i) {
   double su = 0, su2 = 0, sabs = 0, sd = 0, sdp = 0, sa = 0, sa2 = 0, saw = 0, saw2 = 0;
   long long cnt = 0, nclip = 0;
   for (int i = threadIdx.x; i < n_resp; i += kTileThreads) {
@@ -226,70 +205,115 @@ __global__ __launch_bounds__(kTileThreads) void diag_final_kernel(
   *diag_out = d;
 }
 
-// ---- per-row coefficient of the gradient, rectification weight, loss partials -------------------------------------
+// ---- level 1: one tile of one response -> DiagPartial; level 2 in the last workgroup ------------------------
+__global__ __launch_bounds__(kTileThreads) void diag_reduce_kernel(
+    const float* __restrict__ logp_train, const float* __restrict__ logp_roll,
+    const unsigned char* __restrict__ valid, long long n_rows, const long long* __restrict__ cu_rows, int n_resp,
+    const int* __restrict__ tile_off, DiagPartial* partial, int group_size, const float* __restrict__ rewards,
+    ais_params p, float* __restrict__ adv_out, int* __restrict__ count_out, ais_diag* __restrict__ diag_out,
+    const int* __restrict__ status, int* ticket) {
+  __shared__ double lds_d[kTileThreads];
+  __shared__ long long lds_i[kTileThreads];
+  const int b = blockIdx.x;
+  if (b < tile_off[n_resp]) {                        // uniform for the workgroup; the others only take a ticket
+    const int i = find_response(tile_off, n_resp, b);
+    long long lo, hi;
+    response_rows(cu_rows, i, n_rows, lo, hi);
+    const long long r0 = lo + (long long)(b - tile_off[i]) * kTileRows;
+    const long long r1 = min(hi, r0 + kTileRows);
+    const double lnC = log((double)p.C);
+    double su = 0, su2 = 0, sabs = 0, sd = 0, sdp = 0;
+    long long cnt = 0, nclip = 0;
+    for (long long n = r0 + threadIdx.x; n < r1; n += kTileThreads) {
+      if (valid != nullptr && valid[n] == 0) continue;
+      const double lt = (double)logp_train[n], lr = (double)logp_roll[n];
+      const double d = lt - lr;                                            // log rho (Alg. 1, sampler-trainer ratio)
+      const double u = exp(fmin(d, lnC)) - 1.0;                            // w_bar - 1, w_bar = min(rho, C) (Eq. 10)
+      su += u;
+      su2 += u * u;
+      sabs += fabs(d);
+      sd += d;
+      sdp += fabs(exp(lt) - exp(lr));
+      cnt += 1;
+      nclip += (d > lnC) ? 1 : 0;
+    }
+    DiagPartial t;
+    t.su = block_sum(su, lds_d);
+    t.su2 = block_sum(su2, lds_d);
+    t.sabs = block_sum(sabs, lds_d);
+    t.sd = block_sum(sd, lds_d);
+    t.sdp = block_sum(sdp, lds_d);
+    t.cnt = block_sum(cnt, lds_i);
+    t.nclip = block_sum(nclip, lds_i);
+    if (threadIdx.x == 0) partial[b] = t;
+  }
+  // ---- level 2, in the workgroup that finishes last ----
+  if (last_workgroup(ticket))
+    diag_final(partial, tile_off, n_resp, group_size, rewards, p, adv_out, count_out, diag_out, status, lds_d, lds_i);
+}
+
+// ---- per-row coefficient of the gradient, rectification weight, loss ------------------------------------------------
+__device__ void loss_final(const volatile double* partial, int n_tiles, double* __restrict__ loss_out, double* lds_d) {
+  double acc = 0;
+  for (int t = threadIdx.x; t < n_tiles; t += kTileThreads) acc += partial[t];
+  acc = block_sum(acc, lds_d);
+  if (threadIdx.x == 0) *loss_out = acc;
+}
+
 __global__ __launch_bounds__(kTileThreads) void row_coeff_kernel(
     const float* __restrict__ logp_train, const float* __restrict__ logp_roll, const float* __restrict__ logp_old,
     const float* __restrict__ logp_ref, const unsigned char* __restrict__ valid, long long n_rows,
     const long long* __restrict__ cu_rows, int n_resp, const float* __restrict__ adv,
     const int* __restrict__ count, const ais_diag* __restrict__ diag, ais_params p,
-    const int* __restrict__ tile_off, double* __restrict__ partial, float* __restrict__ g_out,
-    float* __restrict__ wtilde_out, float g_scale) {
+    const int* __restrict__ tile_off, double* partial, float* __restrict__ g_out,
+    float* __restrict__ wtilde_out, float g_scale, double* __restrict__ loss_out, int* ticket) {
   __shared__ double lds_d[kTileThreads];
   const int b = blockIdx.x;
-  if (b >= tile_off[n_resp]) return;
-  const int i = find_response(tile_off, n_resp, b);
-  long long lo, hi;
-  response_rows(cu_rows, i, n_rows, lo, hi);
-  const long long r0 = lo + (long long)(b - tile_off[i]) * kTileRows;
-  const long long r1 = min(hi, r0 + kTileRows);
-  const double alpha = diag->alpha;
-  const double a = (double)adv[i];
-  const int cnt = count[i];
-  const double wgt = cnt > 0 ? 1.0 / ((double)n_resp * (double)cnt) : 0.0;   // 1/G and 1/|o_i| of Eq. 19 over all prompts
-  const double lnC = log((double)p.C);
-  const double lo_clip = 1.0 - (double)p.clip_eps, hi_clip = 1.0 + (double)p.clip_eps;
-  const bool kl = (logp_ref != nullptr) && (p.beta_kl > 0.f);
-  double acc = 0;
-  for (long long n = r0 + threadIdx.x; n < r1; n += kTileThreads) {
-    float g = 0.f, wt = 0.f;
-    if (valid == nullptr || valid[n] != 0) {
-      const double lt = (double)logp_train[n];
-      const double wbar = exp(fmin(lt - (double)logp_roll[n], lnC));
-      const double wtilde = 1.0 + alpha * (wbar - 1.0);                       // Eq. 18 / Alg. 1 rectification weight
-      const double rho_on = logp_old != nullptr ? exp(lt - (double)logp_old[n]) : 1.0;
-      const double clipped = fmin(fmax(rho_on, lo_clip), hi_clip);
-      // the unclipped branch is the minimum (ties included) iff the ratio has not left the trust
-      // region on the side the advantage pushes towards
-      const bool active = (a >= 0.0) ? (rho_on <= hi_clip) : (rho_on >= lo_clip);
-      const double s = active ? rho_on * a : clipped * a;
-      double obj = wtilde * s;
-      double dobj = active ? wtilde * a * rho_on : 0.0;
-      if (kl) {
-        const double q = (double)logp_ref[n] - lt;
-        const double eq = exp(q);
-        obj -= (double)p.beta_kl * (eq - q - 1.0);
-        dobj -= (double)p.beta_kl * (1.0 - eq);
+  if (b < tile_off[n_resp]) {                        // uniform for the workgroup; the others only take a ticket
+    const int i = find_response(tile_off, n_resp, b);
+    long long lo, hi;
+    response_rows(cu_rows, i, n_rows, lo, hi);
+    const long long r0 = lo + (long long)(b - tile_off[i]) * kTileRows;
+    const long long r1 = min(hi, r0 + kTileRows);
+    const double alpha = diag->alpha;
+    const double a = (double)adv[i];
+    const int cnt = count[i];
+    const double wgt = cnt > 0 ? 1.0 / ((double)n_resp * (double)cnt) : 0.0;   // 1/G and 1/|o_i| of Eq. 19 over all prompts
+    const double lnC = log((double)p.C);
+    const double lo_clip = 1.0 - (double)p.clip_eps, hi_clip = 1.0 + (double)p.clip_eps;
+    const bool kl = (logp_ref != nullptr) && (p.beta_kl > 0.f);
+    double acc = 0;
+    for (long long n = r0 + threadIdx.x; n < r1; n += kTileThreads) {
+      float g = 0.f, wt = 0.f;
+      if (valid == nullptr || valid[n] != 0) {
+        const double lt = (double)logp_train[n];
+        const double wbar = exp(fmin(lt - (double)logp_roll[n], lnC));
+        const double wtilde = 1.0 + alpha * (wbar - 1.0);                       // Eq. 18 / Alg. 1 rectification weight
+        const double rho_on = logp_old != nullptr ? exp(lt - (double)logp_old[n]) : 1.0;
+        const double clipped = fmin(fmax(rho_on, lo_clip), hi_clip);
+        // the unclipped branch is the minimum (ties included) iff the ratio has not left the trust
+        // region on the side the advantage pushes towards
+        const bool active = (a >= 0.0) ? (rho_on <= hi_clip) : (rho_on >= lo_clip);
+        const double s = active ? rho_on * a : clipped * a;
+        double obj = wtilde * s;
+        double dobj = active ? wtilde * a * rho_on : 0.0;
+        if (kl) {
+          const double q = (double)logp_ref[n] - lt;
+          const double eq = exp(q);
+          obj -= (double)p.beta_kl * (eq - q - 1.0);
+          dobj -= (double)p.beta_kl * (1.0 - eq);
+        }
+        acc -= wgt * obj;
+        g = (float)(wgt * dobj * (double)g_scale);
+        wt = (float)wtilde;
       }
-      acc -= wgt * obj;
-      g = (float)(wgt * dobj * (double)g_scale);
-      wt = (float)wtilde;
+      g_out[n] = g;
+      if (wtilde_out != nullptr) wtilde_out[n] = wt;
     }
-    g_out[n] = g;
-    if (wtilde_out != nullptr) wtilde_out[n] = wt;
+    acc = block_sum(acc, lds_d);
+    if (threadIdx.x == 0) partial[b] = acc;
   }
-  acc = block_sum(acc, lds_d);
-  if (threadIdx.x == 0) partial[b] = acc;
-}
-
-__global__ __launch_bounds__(kTileThreads) void loss_final_kernel(const double* __restrict__ partial,
-                                                                  const int* __restrict__ tile_off, int n_resp,
-                                                                  double* __restrict__ loss_out) {
-  __shared__ double lds_d[kTileThreads];
-  const int n_tiles = tile_off[n_resp];
-  double acc = 0;
-  for (int t = threadIdx.x; t < n_tiles; t += kTileThreads) acc += partial[t];
-  acc = block_sum(acc, lds_d);
-  if (threadIdx.x == 0) *loss_out = acc;
+  if (last_workgroup(ticket)) loss_final(partial, tile_off[n_resp], loss_out, lds_d);
 }
 
 }  // namespace
@@ -298,8 +322,8 @@ WorkspaceLayout workspace_layout(long long n_rows, int n_resp) {
   auto up = [](size_t v) { return (v + 255) & ~size_t(255); };
   WorkspaceLayout w;
   w.max_tiles = (int)((n_rows + kTileRows - 1) / kTileRows) + n_resp;
-  w.tile_off = 0;
-  w.partial = up(w.tile_off + sizeof(int) * (size_t)(n_resp + 1));
+  w.tile_off = 0;                      // int [n_resp + 1] followed by the ticket counter
+  w.partial = up(w.tile_off + sizeof(int) * (size_t)(n_resp + 2));
   w.g = up(w.partial + sizeof(DiagPartial) * (size_t)w.max_tiles);
   w.total = up(w.g + sizeof(float) * (size_t)n_rows);
   return w;
@@ -307,32 +331,31 @@ WorkspaceLayout workspace_layout(long long n_rows, int n_resp) {
 
 int launch_plan(ais_ctx* ctx, const long long* cu_rows, int n_resp, long long n_rows, int* tile_off,
                 int max_tiles) {
-  plan_kernel<<<1, kTileThreads, 0, ctx->stream>>>(cu_rows, n_resp, n_rows, tile_off, max_tiles, ctx->status_dev);
+  plan_kernel<<<1, kTileThreads, 0, ctx->stream>>>(cu_rows, n_resp, n_rows, tile_off, max_tiles, ctx->status_dev,
+                                                   tile_off + n_resp + 1);
   return hip_fail(ctx, hipGetLastError());
 }
 
 int launch_diagnostics(ais_ctx* ctx, const float* logp_train, const float* logp_roll, const unsigned char* valid,
                        long long n_rows, const long long* cu_rows, int n_resp, int group_size,
-                       const float* rewards, const ais_params& p, const int* tile_off, int max_tiles,
+                       const float* rewards, const ais_params& p, int* tile_off, int max_tiles,
                        DiagPartial* partial, float* adv_out, int* count_out, ais_diag* diag_out) {
-  if (max_tiles > 0)
-    diag_partial_kernel<<<max_tiles, kTileThreads, 0, ctx->stream>>>(logp_train, logp_roll, valid, n_rows, cu_rows,
-                                                                     n_resp, tile_off, p.C, partial);
-  diag_final_kernel<<<1, kTileThreads, 0, ctx->stream>>>(partial, tile_off, n_resp, group_size, rewards, p, adv_out,
-                                                         count_out, diag_out, ctx->status_dev);
+  diag_reduce_kernel<<<max_tiles, kTileThreads, 0, ctx->stream>>>(logp_train, logp_roll, valid, n_rows, cu_rows,
+                                                                  n_resp, tile_off, partial, group_size, rewards, p,
+                                                                  adv_out, count_out, diag_out, ctx->status_dev,
+                                                                  tile_off + n_resp + 1);
   return hip_fail(ctx, hipGetLastError());
 }
 
 int launch_row_coeff(ais_ctx* ctx, const float* logp_train, const float* logp_roll, const float* logp_old,
                      const float* logp_ref, const unsigned char* valid, long long n_rows,
                      const long long* cu_rows, int n_resp, const float* adv, const int* count,
-                     const ais_diag* diag, const ais_params& p, const int* tile_off, int max_tiles,
+                     const ais_diag* diag, const ais_params& p, int* tile_off, int max_tiles,
                      double* partial, float* g_out, float* wtilde_out, double* loss_out, float g_scale) {
-  if (max_tiles > 0)
-    row_coeff_kernel<<<max_tiles, kTileThreads, 0, ctx->stream>>>(logp_train, logp_roll, logp_old, logp_ref, valid,
-                                                                  n_rows, cu_rows, n_resp, adv, count, diag, p,
-                                                                  tile_off, partial, g_out, wtilde_out, g_scale);
-  loss_final_kernel<<<1, kTileThreads, 0, ctx->stream>>>(partial, tile_off, n_resp, loss_out);
+  row_coeff_kernel<<<max_tiles, kTileThreads, 0, ctx->stream>>>(logp_train, logp_roll, logp_old, logp_ref, valid,
+                                                                n_rows, cu_rows, n_resp, adv, count, diag, p,
+                                                                tile_off, partial, g_out, wtilde_out, g_scale,
+                                                                loss_out, tile_off + n_resp + 1);
   return hip_fail(ctx, hipGetLastError());
 }
 
