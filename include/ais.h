@@ -245,12 +245,36 @@ int ais_fp8_rollout_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, l
                             long long vocab, long long row_stride, const int* token_ids,
                             const unsigned char* valid, float* logp_roll_out);
 
+/* ---- log-probabilities without materialised logits ------------------------------------------- */
+
+/* log pi_train(o_t) (Alg. 1, "Compute full-precision log-probs ... for all generated tokens") taken
+ * straight from the last hidden states and the output-embedding matrix of the policy:
+ *   z[n, v] = sum_d hidden[n, d] * weight[v, d]   (bf16 inputs, fp32 accumulation on the matrix cores)
+ *   logp_out[n] = inv_temperature * z[n, y_n] - lse_n,  lse_n = log sum_v exp(inv_temperature * z[n, v])
+ * The [n_rows, vocab] logits are folded into a running (max, sum) per token as they are produced and
+ * are never written to memory.
+ *   hidden      [n_rows, hidden_stride] device, bf16; the first d_model entries of each row are read
+ *               (all rows are read, also those with valid == 0)
+ *   weight      [vocab, weight_stride]  device, bf16; row v is the output embedding of token v
+ *   token_ids   [n_rows] device; ignored where valid == 0
+ *   logp_out, lse_out  [n_rows] device fp32; 0 where valid == 0; a row whose token id is outside
+ *               [0, vocab) gets logp 0, its lse, and AIS_STATUS_BAD_TOKEN in the status word
+ * Uses the context workspace (2 * chunks + 1 floats per row, chunks <= 64); nothing is retained.
+ * Errors: dtype other than AIS_BF16 (AIS_ERR_DTYPE); n_rows < 0, vocab < 1, d_model < 8 or not a
+ * multiple of 8 (AIS_ERR_SIZE); a stride < d_model (AIS_ERR_STRIDE); NULL pointers; hidden or weight
+ * not 16-byte aligned or a stride not a multiple of 8 elements (AIS_ERR_ALIGN); inv_temperature
+ * <= 0 or not finite (AIS_ERR_PARAM). */
+int ais_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long hidden_stride, const void* weight,
+                        long long weight_stride, ais_dtype dtype, long long n_rows, long long d_model,
+                        long long vocab, const int* token_ids, const unsigned char* valid,
+                        float inv_temperature, float* logp_out, float* lse_out);
+
 /* ---- measurement helpers -------------------------------------------------------------------- */
 
 /* Kernels whose device time can be read back. */
 typedef enum ais_kernel {
   AIS_K_LOGPROB = 0, AIS_K_DLOGITS = 1, AIS_K_COPY = 2, AIS_K_FP8_QUANT = 3, AIS_K_FP8_DEQUANT = 4,
-  AIS_K_FP8_LOGPROB = 5, AIS_K_FUSED = 6, AIS_K_COUNT_ = 7
+  AIS_K_FP8_LOGPROB = 5, AIS_K_FUSED = 6, AIS_K_LM_HEAD = 7, AIS_K_COUNT_ = 8
 } ais_kernel;
 
 /* With `enable` != 0 every launch of the kernels above is bracketed by HIP events on the

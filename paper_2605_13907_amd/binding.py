@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(PKG, "libais_gfx950.so")
 AIS_BF16, AIS_F32 = 0, 1
 AIS_K_LOGPROB, AIS_K_DLOGITS, AIS_K_COPY, AIS_K_FP8_QUANT, AIS_K_FP8_DEQUANT, AIS_K_FP8_LOGPROB = range(6)
 AIS_K_FUSED = 6
+AIS_K_LM_HEAD = 7
 STATUS_BAD_TOKEN, STATUS_BAD_CU = 1, 2
 
 ERRORS = {
@@ -73,6 +74,7 @@ SYMBOLS = {
     "ais_fp8_quantize_rows": (_I, [_P, _P, _I, _LL, _LL, _LL, _P, _LL, _P]),
     "ais_fp8_dequantize_rows": (_I, [_P, _P, _LL, _P, _LL, _LL, _P, _I, _LL]),
     "ais_fp8_rollout_logprob": (_I, [_P, _P, _I, _LL, _LL, _LL, _P, _P, _P]),
+    "ais_lm_head_logprob": (_I, [_P, _P, _LL, _P, _LL, _I, _LL, _LL, _LL, _P, _P, _F, _P, _P]),
     "ais_profile": (_I, [_P, _I]),
     "ais_profile_read": (_I, [_P, _I, C.POINTER(_F), C.POINTER(_I)]),
     "ais_copy": (_I, [_P, _P, _P, _LL]),
@@ -338,6 +340,31 @@ class AisContext:
         if rc != 0:
             raise AisError(rc, "ais_fp8_rollout_logprob")
         return out
+
+    # ------------------------------------------------------------------ log-probs without materialised logits
+    def lm_head_logprob(self, hidden, weight, token_ids, valid=None, inv_temperature: float = 1.0):
+        """-> (logp [R] fp32, lse [R] fp32) from hidden [R, D] and weight [V, D], both bf16."""
+        for name, t in (("hidden", hidden), ("weight", weight)):
+            if t.dim() != 2 or t.stride(1) != 1:
+                raise ValueError(f"{name} must be 2-D with unit stride along d_model")
+            if t.dtype != torch.bfloat16:
+                raise ValueError(f"{name} must be bfloat16")
+        n_rows, d_model = hidden.shape
+        vocab = weight.shape[0]
+        if weight.shape[1] != d_model:
+            raise ValueError("hidden and weight disagree on d_model")
+        dev = self.device
+        logp = torch.empty(n_rows, dtype=torch.float32, device=dev)
+        lse = torch.empty(n_rows, dtype=torch.float32, device=dev)
+        self._sync_stream()
+        rc = self._lib.ais_lm_head_logprob(
+            self._h, C.c_void_p(hidden.data_ptr()), hidden.stride(0) if n_rows > 1 else max(d_model, hidden.stride(0)),
+            C.c_void_p(weight.data_ptr()), weight.stride(0) if vocab > 1 else max(d_model, weight.stride(0)),
+            AIS_BF16, n_rows, d_model, vocab, _ptr(token_ids, torch.int32, n_rows, "token_ids", dev),
+            _ptr(valid, torch.uint8, n_rows, "valid", dev), float(inv_temperature), _ptr(logp), _ptr(lse))
+        if rc != 0:
+            raise AisError(rc, "ais_lm_head_logprob")
+        return logp, lse
 
     # ------------------------------------------------------------------ helpers
     def read_diag(self, diag: torch.Tensor) -> dict:

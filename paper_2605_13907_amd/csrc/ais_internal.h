@@ -37,6 +37,15 @@ struct WorkspaceLayout {
 };
 WorkspaceLayout workspace_layout(long long n_rows, int n_resp);
 
+// Decomposition of the hidden-state read-out: token blocks x chunks of vocabulary tiles.
+struct LmHeadPlan {
+  int n_tblocks;        // blocks of 256 tokens
+  int n_vtiles;         // tiles of 256 vocabulary entries
+  int n_chunks;         // contiguous chunks the tiles are split into
+  int tiles_per_chunk;  // tiles of every chunk but possibly the last
+};
+LmHeadPlan lm_head_plan(long long n_rows, int vocab, int n_cus);
+
 }  // namespace ais
 
 struct ais_ctx {
@@ -45,6 +54,7 @@ struct ais_ctx {
   void* ws = nullptr;
   size_t ws_bytes = 0;
   int* status_dev = nullptr;
+  int n_cus = 256;               // compute units of the device
   int last_hip_error = 0;
   bool profiling = false;
   struct Timed { hipEvent_t start, stop; int which; };
@@ -96,5 +106,10 @@ int launch_fp8_dequantize(ais_ctx* ctx, const unsigned char* codes, long long co
 int launch_fp8_rollout_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,
                                long long row_stride, const int* token_ids, const unsigned char* valid,
                                float* logp_out);
+
+int launch_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long ld_h, const void* weight, long long ld_w,
+                           long long n_rows, int d_model, int vocab, const int* token_ids,
+                           const unsigned char* valid, float inv_temperature, const LmHeadPlan& plan,
+                           float* part_m, float* part_s, float* zy, float* logp_out, float* lse_out);
 
 }  // namespace ais

@@ -163,6 +163,11 @@ int ais_create(ais_ctx** out, int device, void* hip_stream) {
     delete ctx;
     return AIS_ERR_HIP;
   }
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0)
+    ctx->n_cus = cus;
+  else
+    (void)hipGetLastError();
   int rc = ensure_workspace(ctx, 1 << 20);
   if (rc != AIS_OK) {
     (void)hipFree(ctx->status_dev);
@@ -365,6 +370,37 @@ int ais_fp8_rollout_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, l
   DeviceGuard guard(ctx->device);
   return launch_fp8_rollout_logprob(ctx, logits, dtype, n_rows, (int)vocab, row_stride, token_ids, valid,
                                     logp_roll_out);
+}
+
+int ais_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long hidden_stride, const void* weight,
+                        long long weight_stride, ais_dtype dtype, long long n_rows, long long d_model,
+                        long long vocab, const int* token_ids, const unsigned char* valid, float inv_temperature,
+                        float* logp_out, float* lse_out) {
+  if (dtype != AIS_BF16) return AIS_ERR_DTYPE;
+  if (n_rows < 0 || n_rows > 0x7fffffffLL - 256) return AIS_ERR_SIZE;
+  if (vocab < 1 || vocab > 0x7fffffffLL - 256) return AIS_ERR_SIZE;
+  if (d_model < 8 || d_model > (1 << 20) || d_model % 8 != 0) return AIS_ERR_SIZE;
+  if (hidden_stride < d_model || weight_stride < d_model) return AIS_ERR_STRIDE;
+  if (weight == nullptr) return AIS_ERR_NULL;
+  if (n_rows > 0 && (hidden == nullptr || token_ids == nullptr || logp_out == nullptr || lse_out == nullptr))
+    return AIS_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(hidden) % 16 != 0 || reinterpret_cast<uintptr_t>(weight) % 16 != 0 ||
+      hidden_stride % 8 != 0 || weight_stride % 8 != 0)
+    return AIS_ERR_ALIGN;
+  if (!std::isfinite(inv_temperature) || inv_temperature <= 0.f) return AIS_ERR_PARAM;
+  if (ctx == nullptr) return AIS_ERR_NULL;
+  if (n_rows == 0) return AIS_OK;
+  DeviceGuard guard(ctx->device);
+  const LmHeadPlan plan = lm_head_plan(n_rows, (int)vocab, ctx->n_cus);
+  // workspace: per-chunk partial (max, sum) of every token, and the sampled token's logit
+  const size_t per = sizeof(float) * (size_t)n_rows;
+  int rc = ensure_workspace(ctx, per * (2 * (size_t)plan.n_chunks + 1));
+  if (rc != AIS_OK) return rc;
+  float* part_m = static_cast<float*>(ctx->ws);
+  float* part_s = part_m + (size_t)plan.n_chunks * (size_t)n_rows;
+  float* zy = part_s + (size_t)plan.n_chunks * (size_t)n_rows;
+  return launch_lm_head_logprob(ctx, hidden, hidden_stride, weight, weight_stride, n_rows, (int)d_model, (int)vocab,
+                                token_ids, valid, inv_temperature, plan, part_m, part_s, zy, logp_out, lse_out);
 }
 
 int ais_profile(ais_ctx* ctx, int enable) {

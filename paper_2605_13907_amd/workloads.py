@@ -232,3 +232,59 @@ def generate(shape: RolloutShape, device: str = "cpu", row_chunk: int = 256) -> 
     return RolloutBatch(shape=shape, logits=logits, token_ids=token_ids, valid=valid,
                         cu_rows=cu.to(dev), logp_roll=logp_roll, rewards=rewards.to(dev),
                         lengths=lengths)
+
+
+# ---------------------------------------------------------------------------------------------------------
+# Inputs of the hidden-state read-out: final hidden states and an output-embedding matrix instead of logits.
+
+# d_model of the model families whose vocabularies the workloads above use (public model cards).
+D_MODEL = {"tiny": 64, "qwen3-8b": 4096, "llada-8b": 4096, "qwen3.5-9b": 4096, "long-horizon": 4096}
+
+
+@dataclass
+class ReadoutBatch:
+    """hidden [R, D] and weight [V, D] in bf16, sampled tokens and mask as in RolloutBatch."""
+
+    hidden: torch.Tensor
+    weight: torch.Tensor
+    token_ids: torch.Tensor   # [R] int32; -1 on rows that are not evaluated
+    valid: torch.Tensor       # [R] uint8
+
+
+def generate_readout(shape: RolloutShape, d_model: Optional[int] = None, device: str = "cpu",
+                     n_rows: Optional[int] = None) -> ReadoutBatch:
+    """Seeded hidden states and output embeddings whose logits look like a language model's.
+
+    weight rows ~ N(0, I/D) (unit norm on average).  Every row t has a preferred token m_t and a sharpness
+    b_t ~ U(0, 12): hidden_t = b_t * weight[m_t] / |weight[m_t]|^2 + xi_t with xi_t ~ N(0, I), so the preferred
+    token's logit is b_t + N(0, 1) against a background of roughly N(0, 1 + b_t^2 / D): rows from nearly flat
+    to sharply peaked.  The sampled token is m_t with probability 0.7, else uniform over the vocabulary.  Row structure
+    (number of rows, mask) is the rollout shape's.  All draws are seeded; bulk tensors are drawn on
+    ``device`` and rounded to bf16, and the rounded values are the inputs."""
+    _, valid_cpu, _, _ = layout_of(shape)
+    R = int(valid_cpu.numel()) if n_rows is None else int(n_rows)
+    valid_cpu = valid_cpu[:R]
+    V = shape.vocab
+    D = int(d_model or D_MODEL.get(shape.name.split("/")[0], 64))
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(shape.seed + 77)
+    cgen = torch.Generator(device="cpu")
+    cgen.manual_seed(shape.seed + 78)
+    weight = (torch.randn(V, D, generator=gen, device=dev, dtype=torch.float32) / math.sqrt(D)).to(torch.bfloat16)
+    mode = torch.randint(0, V, (R,), generator=cgen, dtype=torch.int64)
+    sharp = torch.rand(R, generator=cgen, dtype=torch.float32) * 12.0
+    other = torch.randint(0, V, (R,), generator=cgen, dtype=torch.int64)
+    pick = torch.rand(R, generator=cgen, dtype=torch.float32) < 0.7
+    y = torch.where(pick, mode, other).to(torch.int32)
+    y = torch.where(valid_cpu.bool(), y, torch.full_like(y, -1))
+    hidden = torch.empty(R, D, device=dev, dtype=torch.bfloat16)
+    step = 4096
+    for r0 in range(0, R, step):
+        r1 = min(R, r0 + step)
+        wm = weight[mode[r0:r1].to(dev)].to(torch.float32)
+        nrm = (wm * wm).sum(dim=1, keepdim=True).clamp_min(1e-6)
+        noise = torch.randn(r1 - r0, D, generator=gen, device=dev, dtype=torch.float32)
+        b = sharp[r0:r1].to(dev).unsqueeze(1)
+        hidden[r0:r1] = (b * wm / nrm + noise).to(torch.bfloat16)
+    return ReadoutBatch(hidden=hidden, weight=weight, token_ids=y.to(dev), valid=valid_cpu.to(dev))

@@ -121,6 +121,35 @@ def test_loss_grad_argument_checks():
     assert call(dtype=3) == -7
 
 
+def test_lm_head_logprob_argument_checks():
+    lib = B._lib()
+
+    def call(**kw):
+        a = dict(ctx=None, hidden=C.c_void_p(0x1000), ld_h=64, weight=C.c_void_p(0x2000), ld_w=64, dtype=B.AIS_BF16,
+                 n_rows=4, d=64, vocab=100, tok=FAKE, valid=None, inv_t=1.0, logp=FAKE, lse=FAKE)
+        a.update(kw)
+        return lib.ais_lm_head_logprob(a["ctx"], a["hidden"], a["ld_h"], a["weight"], a["ld_w"], a["dtype"],
+                                       a["n_rows"], a["d"], a["vocab"], a["tok"], a["valid"], a["inv_t"],
+                                       a["logp"], a["lse"])
+
+    assert call() == -1                                          # everything fine except the NULL context
+    assert call(dtype=B.AIS_F32) == -7
+    assert call(n_rows=-1) == -2
+    assert call(vocab=0) == -2
+    assert call(d=0) == -2
+    assert call(d=12) == -2                                      # not a multiple of 8
+    assert call(ld_h=56) == -3
+    assert call(ld_w=8) == -3
+    assert call(ld_h=68) == -4                                   # rows would not stay 16-byte aligned
+    assert call(hidden=C.c_void_p(0x1008)) == -4
+    assert call(weight=C.c_void_p(0x2002)) == -4
+    assert call(weight=None) == -1
+    assert call(hidden=None) == -1
+    assert call(lse=None) == -1
+    assert call(inv_t=-1.0) == -5
+    assert call(n_rows=0, hidden=None, tok=None, logp=None, lse=None) == -1
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_LIB", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))

@@ -1,0 +1,157 @@
+"""GPU parity of the hidden-state read-out (ais_lm_head_logprob) against the CPU oracle
+(oracle/lm_head_oracle.py) on the same seeded bits.
+
+Tolerance: the bar of the log-prob step, |gpu - oracle| <= 2e-3 absolute on evaluated rows and exactly 0 on
+the others.  The inputs are bf16, so every product is exact in fp32 and the only error against the fp64
+oracle is the fp32 accumulation over d_model terms (about sqrt(d_model) * 2^-24 * |z|, 1e-5 at d_model = 4096)
+plus the fp32 exp/log of the soft-max; the observed maximum is printed by each test."""
+import numpy as np
+import pytest
+import torch
+
+import oracle.lm_head_oracle as L
+from paper_2605_13907_amd import binding as B
+from paper_2605_13907_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+LOGP_ATOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = B.AisContext()
+    yield c
+    c.close()
+
+
+def f64(t):
+    return t.detach().cpu().to(torch.float64).numpy()
+
+
+def compare(ctx, hidden, weight, y, valid, inv_t=1.0, rows=None):
+    """Runs the GPU path on everything, the oracle on `rows` (all rows if None)."""
+    logp, lse = ctx.lm_head_logprob(hidden, weight, y, valid, inv_t)
+    torch.cuda.synchronize()
+    status = ctx.status()
+    R = hidden.shape[0]
+    sel = np.arange(R) if rows is None else np.asarray(rows)
+    v_np = np.ones(R, bool) if valid is None else valid.cpu().numpy().astype(bool)
+    y_np = y.cpu().numpy().astype(np.int64)
+    y_ok = (y_np >= 0) & (y_np < weight.shape[0])
+    ref_logp, ref_lse = L.token_logprob(f64(hidden[torch.from_numpy(sel).to(hidden.device)]), f64(weight),
+                                        np.where(y_ok, y_np, 0)[sel], v_np[sel], inv_t)
+    got_logp, got_lse = logp.cpu().numpy()[sel], lse.cpu().numpy()[sel]
+    ev = v_np[sel]
+    assert np.all(got_logp[~ev] == 0.0) and np.all(got_lse[~ev] == 0.0)
+    err_lse = np.abs(got_lse[ev] - ref_lse[ev]).max() if ev.any() else 0.0
+    good = ev & y_ok[sel]
+    err_lp = np.abs(got_logp[good] - ref_logp[good]).max() if good.any() else 0.0
+    print(f"max |dlogp| {err_lp:.2e}  max |dlse| {err_lse:.2e}  rows {len(sel)}", flush=True)
+    assert err_lse <= LOGP_ATOL and err_lp <= LOGP_ATOL
+    bad = ev & ~y_ok[sel]
+    assert np.all(got_logp[bad] == 0.0)
+    assert bool(status & 1) == bool((v_np & ~y_ok).any())
+    return logp, lse
+
+
+def make(R, D, V, seed, p_valid=1.0, scale=1.0, device="cuda"):
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    hidden = (torch.randn(R, D, generator=g) * scale).to(torch.bfloat16).to(device)
+    weight = (torch.randn(V, D, generator=g) / np.sqrt(D) * 3.0).to(torch.bfloat16).to(device)
+    y = torch.randint(0, V, (R,), generator=g, dtype=torch.int32).to(device)
+    valid = None
+    if p_valid < 1.0:
+        valid = (torch.rand(R, generator=g) < p_valid).to(torch.uint8).to(device)
+    return hidden, weight, y, valid
+
+
+# several tiles in both directions, ragged tails in rows, vocabulary and d_model, and the degenerate sizes
+SHAPES = [
+    (1, 8, 1), (1, 64, 1000), (3, 8, 2), (256, 64, 256), (257, 64, 257), (300, 72, 1000), (513, 128, 2049),
+    (1000, 200, 700), (640, 512, 5000), (255, 64, 70_000),
+]
+
+
+@pytest.mark.parametrize("R,D,V", SHAPES)
+def test_shapes(ctx, R, D, V):
+    hidden, weight, y, valid = make(R, D, V, seed=R * 7 + D + V, p_valid=0.8 if R > 3 else 1.0)
+    compare(ctx, hidden, weight, y, valid)
+
+
+@pytest.mark.parametrize("inv_t", [0.5, 1.0, 1.7])
+def test_temperature_and_peaked_rows(ctx, inv_t):
+    hidden, weight, y, valid = make(400, 256, 3000, seed=11, scale=4.0)
+    # make half of the rows sharply peaked on their sampled token
+    w_y = weight[y[:200].long()].float()
+    hidden[:200] = (hidden[:200].float() + 6.0 * w_y / (w_y * w_y).sum(1, keepdim=True)).to(torch.bfloat16)
+    compare(ctx, hidden, weight, y, valid, inv_t)
+
+
+def test_deep_contraction(ctx):
+    """d_model = 4096: the accumulation length of the real workloads."""
+    hidden, weight, y, valid = make(512, 4096, 4096, seed=12, p_valid=0.9)
+    compare(ctx, hidden, weight, y, valid)
+
+
+def test_strided_operands(ctx):
+    hidden, weight, y, valid = make(300, 64, 900, seed=13)
+    hs = torch.zeros(300, 96, dtype=torch.bfloat16, device="cuda")
+    ws = torch.full((900, 136), float("nan"), dtype=torch.bfloat16, device="cuda")
+    hs[:, :64] = hidden
+    ws[:, :64] = weight
+    a = compare(ctx, hs[:, :64], ws[:, :64], y, valid)
+    b = ctx.lm_head_logprob(hidden, weight, y, valid)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_bad_tokens_and_masked_rows(ctx):
+    hidden, weight, y, valid = make(300, 64, 500, seed=14, p_valid=0.7)
+    y = y.clone()
+    y[5] = 500
+    y[17] = -3
+    valid[5] = 1
+    valid[17] = 1
+    hidden[torch.nonzero(valid == 0)[0]] = float("nan")          # rows that are not evaluated may hold anything
+    compare(ctx, hidden, weight, y, valid)
+    assert ctx.status() == 0                                      # reading the status cleared it
+
+
+def test_all_rows_masked(ctx):
+    hidden, weight, y, _ = make(70, 64, 300, seed=15)
+    valid = torch.zeros(70, dtype=torch.uint8, device="cuda")
+    logp, lse = ctx.lm_head_logprob(hidden, weight, y, valid)
+    torch.cuda.synchronize()
+    assert not logp.any() and not lse.any() and ctx.status() == 0
+
+
+def test_empty_batch(ctx):
+    hidden, weight, y, _ = make(4, 64, 300, seed=16)
+    logp, lse = ctx.lm_head_logprob(hidden[:0], weight, y[:0], None)
+    assert logp.numel() == 0 and lse.numel() == 0
+
+
+def test_reproducible(ctx):
+    hidden, weight, y, valid = make(700, 128, 3000, seed=17)
+    a = ctx.lm_head_logprob(hidden, weight, y, valid)
+    b = ctx.lm_head_logprob(hidden, weight, y, valid)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_workload_1(ctx):
+    batch = W.generate_readout(W.config(1), device="cuda")
+    compare(ctx, batch.hidden, batch.weight, batch.token_ids, batch.valid)
+
+
+def test_full_size_sampled(ctx):
+    """Workload 2 at full size (41,643 rows, d_model 4096, vocabulary 151,936) in the launch configuration the
+    benchmark times; the oracle evaluates a sample of rows that covers the first and last token block and the
+    block boundaries."""
+    shape = W.config(2)
+    batch = W.generate_readout(shape, device="cuda")
+    R = batch.hidden.shape[0]
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, 257, R - 257, R - 256, R - 1], rng.integers(0, R, 40)]))
+    compare(ctx, batch.hidden, batch.weight, batch.token_ids, batch.valid, rows=rows)
