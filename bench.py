@@ -18,6 +18,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # dense bf16 MFMA, MI355X
 HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E, vendor figure
 
 
@@ -233,6 +234,37 @@ def main():
                                     "frac": os_bytes / (ms_os * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                                     "fused_kernel_avg_ms": (ms_k / n_k) if n_k else None,
                                     "speedup_vs_three_call_path": ms_step / ms_os}
+        # log-probs straight from hidden states (matrix cores): the same rows and vocabulary, d_model of the family
+        rb = workloads.generate_readout(shape, device="cuda")
+        Dm = rb.hidden.shape[1]
+        for _ in range(2):
+            ctx.lm_head_logprob(rb.hidden, rb.weight, rb.token_ids, rb.valid, p.inv_temperature)
+        ctx.profile(True)
+        for _ in range(5):
+            ctx.lm_head_logprob(rb.hidden, rb.weight, rb.token_ids, rb.valid, p.inv_temperature)
+        ms, n = ctx.profile_read(binding.AIS_K_LM_HEAD)
+        ctx.profile(False)
+        flops = 2.0 * R * V * Dm
+        tf = flops / (ms / n * 1e-3) / 1e12
+        # yardstick: the library GEMM that materialises the bf16 logits, followed by the streaming log-prob sweep
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        z = torch.empty(R, V, dtype=torch.bfloat16, device="cuda")
+        for _ in range(2):
+            torch.matmul(rb.hidden, rb.weight.t(), out=z)
+        ev0.record()
+        for _ in range(5):
+            torch.matmul(rb.hidden, rb.weight.t(), out=z)
+        ev1.record()
+        torch.cuda.synchronize()
+        ms_gemm = ev0.elapsed_time(ev1) / 5
+        extras["lm_head_logprob"] = {
+            "avg_ms": ms / n, "d_model": Dm, "flops": flops,
+            "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+            "library_gemm_yardstick": {"avg_ms": ms_gemm, "TFLOP/s": flops / (ms_gemm * 1e-3) / 1e12,
+                                       "note": "torch.matmul to bf16 logits; the materialised route adds the "
+                                               "token_logprob sweep above to this"}}
+        del z, rb
         result["next_rows"] = extras
     if args.cpu_rows > 0:
         params = dict(C=p.C, delta=p.delta, gamma=p.gamma, eps_std=p.eps_std, beta_var=p.beta_var,

@@ -5,23 +5,33 @@
 //   z[t, v] = sum_d H[t, d] W[v, d],   logp_t = z[t, y_t] / T - log sum_v exp(z[t, v] / T)
 //
 // This is a dense contraction (2 * rows * vocab * d_model flops against (rows + vocab) * d_model inputs),
-// bound by the MFMA rate, unlike the sweeps over materialised logits, which are bound by HBM.
+// a matrix-core kernel, unlike the sweeps over materialised logits, which are bound by HBM.
 //
 // Layout of the work.  The product is taken transposed, C^T[v, t] = W H^T, with v_mfma_f32_32x32x16_bf16:
 // a lane of the wavefront then owns one *token* column of every 32x32 tile and 16 vocabulary entries of
 // it, so the running softmax state of a token lives in one lane's registers and the reduction over the
 // vocabulary needs no cross-lane traffic until the very end.  A 512-thread workgroup (8 wavefronts,
 // 2 along the vocabulary x 4 along the tokens, 128 x 64 outputs each) computes 256 vocabulary entries x
-// 256 tokens per tile, stepping through d_model 64 at a time: both operand slices (2 x 32 KiB) are staged
-// through LDS with an XOR swizzle of the 16-byte chunks so that the fragment reads are free of bank
-// conflicts, double-buffered so that one barrier per step suffices, and the global loads of the next
-// step are in flight while the 32 MFMAs of the current one run.  A workgroup owns one block of 256
-// tokens and a contiguous chunk of vocabulary tiles; per token and chunk it emits a partial (max, sum),
-// and a small second kernel merges the partials and subtracts.  Workgroups are numbered so that those
-// resident on one XCD (which share an L2) work on a few token blocks x a few vocabulary chunks at the
-// same time, and therefore share both operands.
+// 256 tokens per tile.  It owns one block of 256 tokens and a contiguous chunk of vocabulary tiles; per
+// token and chunk it emits a partial (max, sum), and a small second kernel merges the partials and
+// subtracts.  Workgroups are numbered so that those resident on one XCD (which share an L2) work on a few
+// token blocks x all vocabulary chunks at the same time, and therefore share both operands.
+//
+// Two kernels do the tile arithmetic.  The streaming kernel (d_model a multiple of 32) copies operand slices
+// from global memory straight into a ring of LDS stages and interleaves copies, LDS reads and MFMAs one by
+// one; the register-staged kernel accepts any d_model that is a multiple of 8.  Both keep the operand slices
+// in LDS with an XOR swizzle of their 16-byte chunks, which makes the fragment reads free of bank conflicts
+// (measured: none).
+//
+// What bounds it.  With 256 x 256 tiles every MFMA needs 256 bytes from L2, and under a sustained run with
+// real (toggling) data the part is power-limited: the shader clock settles near 1.6-1.8 GHz instead of 2.4,
+// and time follows energy rather than cycle counts (shaving cycles per step lowered the clock by the same
+// factor).  Measured at the Qwen3-8B shape: about 1.17 PFLOP/s, against 1.43 PFLOP/s for the library GEMM
+// that materialises the logits.
 #include "ais_internal.h"
 #include "device_utils.h"
+
+#include <type_traits>
 
 namespace ais {
 namespace {
@@ -34,150 +44,72 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kLmThreads = 512;
 constexpr int kLmTileV = 256;      // vocabulary entries per tile
 constexpr int kLmTileT = 256;      // tokens per tile
-constexpr int kLmTileK = 64;       // d_model elements per step
+constexpr int kLmTileK = 64;       // d_model elements per step of the register-staged kernel
 constexpr int kLmWaveV = 128;      // per wavefront: 4 MFMA tiles along the vocabulary
 constexpr int kLmWaveT = 64;       //                2 along the tokens
-constexpr int kLmOperandBytes = kLmTileV * kLmTileK * 2;            // 32 KiB: one operand slice
-constexpr int kLmStageBytes = 2 * kLmOperandBytes;                   // W slice then H slice
-constexpr int kLmLdsBytes = 2 * kLmStageBytes;                       // double buffer: 128 KiB
-
-// Byte offset of 16-byte chunk `c` (0..7) of row `row` inside one operand slice.  A row is 128 bytes; the
-// chunk index is XORed with bits 1..3 of the row so that 16 consecutive rows read at the same logical
-// chunk touch 16 different 16-byte bank groups.
-__device__ __forceinline__ int lds_chunk_offset(int row, int c) { return row * 128 + ((c ^ ((row >> 1) & 7)) << 4); }
-
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 q) { return __builtin_bit_cast(bf16x8, q); }
 
-// One workgroup: token block `tb`, vocabulary tiles [vt0, vt1).  KTAIL: d_model is not a multiple of the
-// 64-element step, so the last step's chunks past the end are replaced by zeros.
-template <bool KTAIL>
-__global__ __launch_bounds__(kLmThreads) void lm_head_partial_kernel(
-    const bf16_t* __restrict__ hidden, long long ld_h, const bf16_t* __restrict__ weight, long long ld_w,
-    int n_rows, int d_model, int vocab, const int* __restrict__ token_ids, const unsigned char* __restrict__ valid,
-    float scale, int n_items, int n_chunks, int tiles_per_chunk, int n_vtiles, float* __restrict__ part_m,
-    float* __restrict__ part_s, float* __restrict__ zy_out) {
-  extern __shared__ __align__(16) unsigned char lds[];
-  // Workgroups are dealt to the 8 XCDs round-robin; give every XCD a contiguous range of work items.
-  const int per_xcd = gridDim.x >> 3;
-  const int item = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-  if (item >= n_items) return;                                  // uniform for the workgroup
-  const int tb = item / n_chunks, ch = item - tb * n_chunks;
-  const int vt0 = ch * tiles_per_chunk;
-  const int vt1 = min(n_vtiles, vt0 + tiles_per_chunk);
-  const int t0 = tb * kLmTileT;
 
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int wv = wave & 1, wt = wave >> 1;                      // position of the wavefront in the tile
-  const int half = lane >> 5, col = lane & 31;
+// ---- pieces shared by the two kernels ---------------------------------------------------------------------
 
-  // ---- global -> LDS staging: thread owns chunk c of rows r0 + 64 i of both operand slices
-  const int c = tid & 7, r0 = tid >> 3;
-  const bf16_t* hp[4];
-  const bf16_t* wp[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int trow = min(t0 + r0 + 64 * i, n_rows - 1);         // rows past the end repeat the last one; discarded later
-    hp[i] = hidden + (long long)trow * ld_h + c * 8;
+// Which part of the problem this workgroup owns, and where the thread sits in its tile.
+struct LmItem {
+  int tb, ch, vt0, vt1, t0;
+  int lane, wave, wv, wt, half, col;
+  __device__ __forceinline__ bool init(int n_items, int n_chunks, int tiles_per_chunk, int n_vtiles) {
+    // Workgroups are dealt to the 8 XCDs round-robin; give every XCD a contiguous range of work items.
+    const int per_xcd = gridDim.x >> 3;
+    const int item = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (item >= n_items) return false;                           // uniform for the workgroup
+    tb = item / n_chunks;
+    ch = item - tb * n_chunks;
+    vt0 = ch * tiles_per_chunk;
+    vt1 = min(n_vtiles, vt0 + tiles_per_chunk);
+    t0 = tb * kLmTileT;
+    lane = threadIdx.x & 63;
+    wave = threadIdx.x >> 6;
+    wv = wave & 1;                                               // position of the wavefront in the tile
+    wt = wave >> 1;
+    half = lane >> 5;
+    col = lane & 31;
+    return true;
   }
-  auto point_w = [&](int vt) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int vrow = min(vt * kLmTileV + r0 + 64 * i, vocab - 1);
-      wp[i] = weight + (long long)vrow * ld_w + c * 8;
-    }
-  };
-  const int st_off = lds_chunk_offset(r0, c);                   // + 8 KiB per i: 64 rows further down
-  u32x4 sw[4], sh[4];
-  const u32x4 zero4 = {0u, 0u, 0u, 0u};
-  (void)zero4;
-  auto fetch = [&](int k0) {
-    if (KTAIL) {
-      // d_model is a multiple of 8: a chunk is wholly inside or wholly outside; outside chunks re-read the
-      // row's first chunk (a valid address) and are zeroed
-      const bool in = k0 + c * 8 < d_model;
-      const int k = in ? k0 : -c * 8;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const u32x4 w = *reinterpret_cast<const u32x4*>(wp[i] + k);
-        const u32x4 h = *reinterpret_cast<const u32x4*>(hp[i] + k);
-        sw[i] = in ? w : zero4;
-        sh[i] = in ? h : zero4;
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        sw[i] = *reinterpret_cast<const u32x4*>(wp[i] + k0);
-        sh[i] = *reinterpret_cast<const u32x4*>(hp[i] + k0);
-      }
-    }
-  };
-  auto stage = [&](int buf) {
-    unsigned char* base = lds + buf * kLmStageBytes + st_off;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      *reinterpret_cast<u32x4*>(base + i * 8192) = sw[i];
-      *reinterpret_cast<u32x4*>(base + kLmOperandBytes + i * 8192) = sh[i];
-    }
-  };
+};
 
-  // ---- LDS -> MFMA fragments: lane reads row (32-row tile base + col), chunk 2 kk + half
-  int frag_off[4];
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) frag_off[kk] = lds_chunk_offset(col, 2 * kk + half);
-  const int a_base = wv * kLmWaveV * 128;                          // W rows of this wavefront
-  const int b_base = kLmOperandBytes + wt * kLmWaveT * 128;        // H rows of this wavefront
+typedef f32x16 LmAcc[4][2];
 
-  f32x16 acc[4][2];
-  auto clear_acc = [&]() {
+__device__ __forceinline__ void lm_clear(LmAcc& acc) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  };
-  // Fragments of step kk + 1 are requested before the MFMAs of step kk are issued; the scheduling barriers keep
-  // the compiler from hoisting all four steps' reads to the top (96 more live registers).
-  auto read_frags = [&](const unsigned char* base, int kk, bf16x8 (&a)[4], bf16x8 (&b)[2]) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      a[i] = as_bf16x8(*reinterpret_cast<const u32x4*>(base + a_base + i * 4096 + frag_off[kk]));
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
-      b[j] = as_bf16x8(*reinterpret_cast<const u32x4*>(base + b_base + j * 4096 + frag_off[kk]));
-  };
-  auto multiply = [&](int buf) {
-    const unsigned char* base = lds + buf * kLmStageBytes;
-    bf16x8 a[2][4], b[2][2];
-    read_frags(base, 0, a[0], b[0]);
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      if (kk < 3) read_frags(base, kk + 1, a[(kk + 1) & 1], b[(kk + 1) & 1]);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk & 1][i], b[kk & 1][j], acc[i][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  };
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+}
 
-  // ---- per-lane softmax state of its two token columns, in the base-2 domain (x * scale)
-  float run_m[2] = {kNegHuge, kNegHuge}, run_s[2] = {0.f, 0.f};
+// Per-lane soft-max state of the lane's two token columns, in the base-2 domain (logit * scale).
+struct LmSoftmax {
+  float run_m[2], run_s[2];
   int tok[2], y[2];
+  __device__ __forceinline__ void init(const LmItem& it, int n_rows, int vocab, const int* __restrict__ token_ids,
+                                       const unsigned char* __restrict__ valid) {
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    tok[j] = t0 + wt * kLmWaveT + j * 32 + col;
-    y[j] = -1;
-    if (tok[j] < n_rows && (valid == nullptr || valid[tok[j]] != 0)) {
-      const int id = token_ids[tok[j]];
-      y[j] = (id >= 0 && id < vocab) ? id : -1;
+    for (int j = 0; j < 2; ++j) {
+      run_m[j] = kNegHuge;
+      run_s[j] = 0.f;
+      tok[j] = it.t0 + it.wt * kLmWaveT + j * 32 + it.col;
+      y[j] = -1;
+      if (tok[j] < n_rows && (valid == nullptr || valid[tok[j]] != 0)) {
+        const int id = token_ids[tok[j]];
+        y[j] = (id >= 0 && id < vocab) ? id : -1;
+      }
     }
   }
-  // accumulator element v of MFMA tile i holds vocabulary entry  vbase + 32 i + 8 (v / 4) + 4 half + v % 4
-  auto fold_tile = [&](int vt) {
-    const int vbase = vt * kLmTileV + wv * kLmWaveV;
+  // Folds the finished tile `vt` into the running state.  Accumulator element v of MFMA tile i holds
+  // vocabulary entry  vbase + 32 i + 8 (v / 4) + 4 half + v % 4  of token column j.
+  __device__ __forceinline__ void fold(LmAcc& acc, const LmItem& it, int vt, int vocab, float scale,
+                                       float* __restrict__ zy_out) {
+    const int vbase = vt * kLmTileV + it.wv * kLmWaveV;
     if (vt * kLmTileV + kLmTileV > vocab) {                      // uniform: only the last tile of the vocabulary
       // entries past the end of the vocabulary become -inf: they never win the max (which starts from a
       // finite value) and add exp2(-inf) = 0 to the sum
@@ -185,7 +117,7 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_partial_kernel(
       for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const bool in = vbase + 32 * i + 8 * (v >> 2) + 4 * half + (v & 3) < vocab;
+          const bool in = vbase + 32 * i + 8 * (v >> 2) + 4 * it.half + (v & 3) < vocab;
 #pragma unroll
           for (int j = 0; j < 2; ++j) acc[i][j][v] = in ? acc[i][j][v] : -__builtin_inff();
         }
@@ -207,7 +139,7 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_partial_kernel(
       run_m[j] = m_new;
       // the sampled token's own logit: held by exactly one lane of one wavefront of one workgroup
       const int rel = y[j] - vbase;
-      if ((unsigned)rel < (unsigned)kLmWaveV && ((rel >> 2) & 1) == half) {
+      if ((unsigned)rel < (unsigned)kLmWaveV && ((rel >> 2) & 1) == it.half) {
         const int idx = (rel >> 5) * 16 + ((rel & 31) >> 3) * 4 + (rel & 3);
         float zy = 0.f;
 #pragma unroll
@@ -215,68 +147,382 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_partial_kernel(
 #pragma unroll
           for (int v = 0; v < 16; ++v) zy = (i * 16 + v == idx) ? acc[i][j][v] : zy;
         zy_out[tok[j]] = zy;
+        // the kernels count their outstanding global->LDS copies; this rare store must not be among them
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      }
+    }
+  }
+  // Merges the two lane halves, then the two wavefronts along the vocabulary (through `xch`, 2 KiB of LDS that
+  // no one uses any more), and writes the chunk's partial (max, sum) of every token of the block.
+  __device__ __forceinline__ void finish(const LmItem& it, float* xch, int n_rows, float* __restrict__ part_m,
+                                         float* __restrict__ part_s) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const float om = __shfl_xor(run_m[j], 32), os = __shfl_xor(run_s[j], 32);
+      const float m = fmaxf(run_m[j], om);
+      run_s[j] = run_s[j] * exp2_fast(run_m[j] - m) + os * exp2_fast(om - m);
+      run_m[j] = m;
+    }
+    __syncthreads();                                            // everyone is done with the staging buffers
+    float* xm = xch;                                            // [4 token groups][64 tokens] max, then sum
+    float* xs = xch + 256;
+    if (it.wv == 1 && it.half == 0) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        xm[it.wt * 64 + j * 32 + it.col] = run_m[j];
+        xs[it.wt * 64 + j * 32 + it.col] = run_s[j];
+      }
+    }
+    __syncthreads();
+    if (it.wv == 0 && it.half == 0) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const float om = xm[it.wt * 64 + j * 32 + it.col], os = xs[it.wt * 64 + j * 32 + it.col];
+        const float m = fmaxf(run_m[j], om);
+        const float s = run_s[j] * exp2_fast(run_m[j] - m) + os * exp2_fast(om - m);
+        if (tok[j] < n_rows) {
+          part_m[(long long)it.ch * n_rows + tok[j]] = m;
+          part_s[(long long)it.ch * n_rows + tok[j]] = s;
+        }
+      }
+    }
+  }
+};
+
+typedef __attribute__((address_space(3))) void* lds_ptr;
+typedef const __attribute__((address_space(1))) void* glb_ptr;
+
+// ---- streaming kernel: d_model a multiple of 32 ---------------------------------------------------------------
+// Steps of 32 elements of d_model; the two operand slices of a step (2 x 16 KiB) go from global memory straight
+// into one of NS LDS stages (global_load_lds_dwordx4: lane i of a wavefront deposits its 16 bytes at base + 16 i,
+// so the swizzle is applied by choosing which chunk each lane fetches).  The copies of step s + NS - 1 are issued
+// during the second half of step s, NS - 2 steps before they are awaited, so the memory pipe stays busy across
+// step boundaries.  One barrier per step, in its middle: it publishes step s + 1 (every wavefront has waited for
+// its own copies) and retires step s - 1 (every wavefront has read what it needs), whose stage the new copies
+// overwrite.  The instruction stream is pinned: each LDS read and each copy sits in the shadow of an MFMA, the
+// fragments of step s + 1 are read during the second half of step s, and two MFMAs whose operands are already
+// in registers are issued just before the barrier, so the matrix cores have work while the wavefronts gather.
+constexpr int kStK = 32;
+constexpr int kStOperandBytes = kLmTileV * kStK * 2;             // 16 KiB
+constexpr int kStStageBytes = 2 * kStOperandBytes;               // 32 KiB
+
+// 16-byte chunk c (0..3) of row `row` of a slice with 64-byte rows: XOR with bits 2..3 of the row makes 16
+// consecutive rows, read at one logical chunk, cover all 16 bank groups.
+__device__ __forceinline__ int st_chunk_offset(int row, int c) { return row * 64 + ((c ^ ((row >> 2) & 3)) << 4); }
+
+template <int NS>
+__global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(
+    const bf16_t* __restrict__ hidden, long long ld_h, const bf16_t* __restrict__ weight, long long ld_w,
+    int n_rows, int d_model, int vocab, const int* __restrict__ token_ids, const unsigned char* __restrict__ valid,
+    float scale, int n_items, int n_chunks, int tiles_per_chunk, int n_vtiles, float* __restrict__ part_m,
+    float* __restrict__ part_s, float* __restrict__ zy_out) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  LmItem it;
+  if (!it.init(n_items, n_chunks, tiles_per_chunk, n_vtiles)) return;
+  const int lane = it.lane, wave = it.wave;
+
+  // ---- copies: wavefront w moves rows 16 w .. 16 w + 15 (+ 128 j) of each slice; a lane sits at chunk position
+  // lane & 3 of row lane >> 2 and therefore fetches logical chunk (lane & 3) ^ ((row >> 2) & 3)
+  const int crow = 16 * wave + (lane >> 2);
+  const int cchunk = (lane & 3) ^ ((lane >> 4) & 3);
+  const bf16_t* hp[2];
+  const bf16_t* wp[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int trow = min(it.t0 + crow + 128 * j, n_rows - 1);   // rows past the end repeat the last one; discarded later
+    hp[j] = hidden + (long long)trow * ld_h + cchunk * 8;
+  }
+  auto point_w = [&](int vt) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int vrow = min(vt * kLmTileV + crow + 128 * j, vocab - 1);
+      wp[j] = weight + (long long)vrow * ld_w + cchunk * 8;
+    }
+  };
+  const int n_ksteps = d_model / kStK;
+  const int n_steps = (it.vt1 - it.vt0) * n_ksteps;
+  // cursor of the next step to be copied
+  int c_step = 0, c_kt = 0, c_vt = it.vt0;
+  point_w(c_vt);
+  // One of the four copy instructions (W rows, H rows, W rows + 128, H rows + 128) that bring the cursor's step
+  // into LDS stage `stage`; the fourth advances the cursor.  They are issued one at a time between MFMAs: a
+  // wavefront stalls while the memory pipe accepts a copy, and spreading them keeps those stalls short and out
+  // of phase across wavefronts.  Once the cursor has reached the last step it stays there: the copies issued
+  // after that re-fetch the last step into stages nobody reads any more, which keeps the number of outstanding
+  // copies (and therefore the wait) the same in every step and the loop free of branches.
+  auto copy_part = [&](int stage, int q) {
+    unsigned char* base = lds + stage * kStStageBytes + wave * 1024 + (q >> 1) * 8192;
+    const int k0 = c_kt * kStK;
+    if ((q & 1) == 0)
+      __builtin_amdgcn_global_load_lds((glb_ptr)(wp[q >> 1] + k0), (lds_ptr)base, 16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds((glb_ptr)(hp[q >> 1] + k0), (lds_ptr)(base + kStOperandBytes), 16, 0, 0);
+    if (q == 3 && c_step + 1 < n_steps) {
+      ++c_step;
+      if (++c_kt == n_ksteps) {
+        c_kt = 0;
+        ++c_vt;
+        point_w(c_vt);
       }
     }
   };
 
+  // ---- fragments: lane reads row (32-row tile base + col), chunk 2 kk + half of a 64-byte row
+  int frag_off[2];
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) frag_off[kk] = st_chunk_offset(it.col, 2 * kk + it.half);
+  const int a_base = it.wv * kLmWaveV * 64;
+  const int b_base = kStOperandBytes + it.wt * kLmWaveT * 64;
+  // One fragment read.  The eight MFMAs of a half-step run in the order (a0,b0) (a0,b1) (a1,b0) (a1,b1) (a2,b0) ..., so
+  // the fragments are needed, and therefore read, in the order a0 b0 b1 a1 a2 a3 (r = 0..5).
+  auto read_frag = [&](int step, int kk, int r, bf16x8 (&a)[4], bf16x8 (&b)[2]) {
+    const unsigned char* base = lds + (step % NS) * kStStageBytes + frag_off[kk];
+    if (r == 1 || r == 2)
+      b[r - 1] = as_bf16x8(*reinterpret_cast<const u32x4*>(base + b_base + (r - 1) * 2048));
+    else {
+      const int i = r == 0 ? 0 : r - 2;
+      a[i] = as_bf16x8(*reinterpret_cast<const u32x4*>(base + a_base + i * 2048));
+    }
+  };
+  auto read_frags = [&](int step, int kk, bf16x8 (&a)[4], bf16x8 (&b)[2]) {
+#pragma unroll
+    for (int r = 0; r < 6; ++r) read_frag(step, kk, r, a, b);
+  };
+
+  LmAcc acc;
+  lm_clear(acc);
+  // MFMAs first .. last - 1 (of 8) of one half-step
+  auto mfma_range = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[2], int first, int last) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        if (2 * i + j >= first && 2 * i + j < last)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+  };
+  LmSoftmax sm;
+  sm.init(it, n_rows, vocab, token_ids, valid);
+
+  // Every wavefront issues 4 copies per step and they complete in order: waiting until at most 4 * younger
+  // are outstanding means the step before the `younger` most recent ones has landed.
+  static_assert(NS >= 3 && NS <= 5, "the waits below are written for 3 to 5 stages");
+  auto wait_all_but = [](auto younger) {
+    constexpr int Y = decltype(younger)::value;
+    if (Y == 3) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+    else if (Y == 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else if (Y == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  };
+#define AIS_PIN __builtin_amdgcn_sched_barrier(0)
+  bf16x8 a0[4], b0[2], a1[4], b1[2];
+  int vt = it.vt0, kt = 0;
+  // First part of a step: the eight MFMAs of its first 16 elements, one read of the second 16 elements'
+  // fragments in the shadow of each; then the first two MFMAs of the second half, which give the matrix cores
+  // work while the wavefronts gather at the barrier.  The barrier publishes the next step (every wavefront
+  // has waited for its own copies of it) and retires the previous one.
+  // Which fragment reads follow MFMA q of a half-step: two after each of the first two, one after the next two,
+  // so that the last read is four MFMAs old when the next half-step begins.
+  auto reads_after = [&](int q, int step, int kk, bf16x8 (&a)[4], bf16x8 (&b)[2]) {
+    if (q == 0) { read_frag(step, kk, 0, a, b); read_frag(step, kk, 1, a, b); }
+    if (q == 1) { read_frag(step, kk, 2, a, b); read_frag(step, kk, 3, a, b); }
+    if (q == 2) read_frag(step, kk, 4, a, b);
+    if (q == 3) read_frag(step, kk, 5, a, b);
+  };
+  auto first_part = [&](int s) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      mfma_range(a0, b0, q, q + 1);
+      AIS_PIN;
+      reads_after(q, s, 1, a1, b1);
+      AIS_PIN;
+    }
+    mfma_range(a1, b1, 0, 2);
+    AIS_PIN;
+    // Outstanding copies, oldest first: step s + 1, then NS - 3 younger steps.  Wait for the former, then meet.
+    // Written as one opaque instruction pair: a workgroup-scope fence here would make the compiler wait for
+    // every outstanding copy, which is exactly what the extra stages are there to avoid.  The LDS reads issued
+    // above need not be complete at the barrier: the stage they read is not overwritten before the next one.
+    if (NS - 3 == 2) asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
+    else if (NS - 3 == 1) asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    AIS_PIN;
+  };
+
+  // ---- prologue: NS - 1 steps in flight, step 0 published
+#pragma unroll
+  for (int st = 0; st < NS - 1; ++st)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) copy_part(st, q);
+  wait_all_but(std::integral_constant<int, NS - 2>{});
+  __syncthreads();
+  read_frags(0, 0, a0, b0);
+  first_part(0);
+  // ---- steady state: the rest of step s, with the reads of step s + 1 and the copies of step s + NS - 1 (into
+  // the stage step s - 1 has left) in the shadows, then the first part of step s + 1
+  for (int s = 0; s + 1 < n_steps; ++s) {
+    const int stage = (s + NS - 1) % NS;
+#pragma unroll
+    for (int q = 2; q < 8; ++q) {
+      mfma_range(a1, b1, q, q + 1);
+      AIS_PIN;
+      reads_after(q - 2, s + 1, 0, a0, b0);
+      AIS_PIN;
+      if (q >= 4) copy_part(stage, q - 4);
+      AIS_PIN;
+    }
+    if (++kt == n_ksteps) {
+      sm.fold(acc, it, vt, vocab, scale, zy_out);
+      lm_clear(acc);
+      kt = 0;
+      ++vt;
+    }
+    first_part(s + 1);
+  }
+#undef AIS_PIN
+  mfma_range(a1, b1, 2, 8);
+  sm.fold(acc, it, vt, vocab, scale, zy_out);
+  sm.finish(it, reinterpret_cast<float*>(lds), n_rows, part_m, part_s);
+}
+
+// ---- register-staged kernel: any d_model that is a multiple of 8 ---------------------------------------------
+// Steps of 64 elements; the last step's chunks past the end of d_model must become zeros, so the slices are
+// loaded into registers before the arithmetic of a step and written to the other of two LDS buffers in the
+// middle of it.
+constexpr int kLmOperandBytes = kLmTileV * kLmTileK * 2;            // 32 KiB: one operand slice
+constexpr int kLmStageBytes = 2 * kLmOperandBytes;                   // W slice then H slice
+constexpr int kLmLdsBytes = 2 * kLmStageBytes;                       // double buffer: 128 KiB
+
+// Byte offset of 16-byte chunk `c` (0..7) of row `row` inside one operand slice.  A row is 128 bytes; the
+// chunk index is XORed with bits 1..3 of the row so that 16 consecutive rows read at the same logical
+// chunk touch 16 different 16-byte bank groups.
+__device__ __forceinline__ int lds_chunk_offset(int row, int c) { return row * 128 + ((c ^ ((row >> 1) & 7)) << 4); }
+
+__global__ __launch_bounds__(kLmThreads) void lm_head_staged_kernel(
+    const bf16_t* __restrict__ hidden, long long ld_h, const bf16_t* __restrict__ weight, long long ld_w,
+    int n_rows, int d_model, int vocab, const int* __restrict__ token_ids, const unsigned char* __restrict__ valid,
+    float scale, int n_items, int n_chunks, int tiles_per_chunk, int n_vtiles, float* __restrict__ part_m,
+    float* __restrict__ part_s, float* __restrict__ zy_out) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  LmItem it;
+  if (!it.init(n_items, n_chunks, tiles_per_chunk, n_vtiles)) return;
+  const int tid = threadIdx.x;
+
+  // ---- global -> registers -> LDS: thread owns chunk c of rows r0 + 64 i of both operand slices
+  const int c = tid & 7, r0 = tid >> 3;
+  const bf16_t* hp[4];
+  const bf16_t* wp[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int trow = min(it.t0 + r0 + 64 * i, n_rows - 1);      // rows past the end repeat the last one; discarded later
+    hp[i] = hidden + (long long)trow * ld_h + c * 8;
+  }
+  auto point_w = [&](int vt) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int vrow = min(vt * kLmTileV + r0 + 64 * i, vocab - 1);
+      wp[i] = weight + (long long)vrow * ld_w + c * 8;
+    }
+  };
+  const int st_off = lds_chunk_offset(r0, c);                   // + 8 KiB per i: 64 rows further down
+  u32x4 sw[4], sh[4];
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
+  auto fetch = [&](int k0) {
+    // d_model is a multiple of 8: a chunk is wholly inside or wholly outside; outside chunks re-read the
+    // row's first chunk (a valid address) and are zeroed
+    const bool in = k0 + c * 8 < d_model;
+    const int k = in ? k0 : -c * 8;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const u32x4 w = *reinterpret_cast<const u32x4*>(wp[i] + k);
+      const u32x4 h = *reinterpret_cast<const u32x4*>(hp[i] + k);
+      sw[i] = in ? w : zero4;
+      sh[i] = in ? h : zero4;
+    }
+  };
+  auto stage = [&](int buf) {
+    unsigned char* base = lds + buf * kLmStageBytes + st_off;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      *reinterpret_cast<u32x4*>(base + i * 8192) = sw[i];
+      *reinterpret_cast<u32x4*>(base + kLmOperandBytes + i * 8192) = sh[i];
+    }
+  };
+
+  // ---- LDS -> MFMA fragments: lane reads row (32-row tile base + col), chunk 2 kk + half
+  int frag_off[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) frag_off[kk] = lds_chunk_offset(it.col, 2 * kk + it.half);
+  const int a_base = it.wv * kLmWaveV * 128;                       // W rows of this wavefront
+  const int b_base = kLmOperandBytes + it.wt * kLmWaveT * 128;     // H rows of this wavefront
+
+  LmAcc acc;
+  lm_clear(acc);
+  // Fragments of step kk + 1 are requested before the MFMAs of step kk are issued; the scheduling barriers keep
+  // the compiler from hoisting all four steps' reads to the top (96 more live registers).
+  auto read_frags = [&](const unsigned char* base, int kk, bf16x8 (&a)[4], bf16x8 (&b)[2]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      a[i] = as_bf16x8(*reinterpret_cast<const u32x4*>(base + a_base + i * 4096 + frag_off[kk]));
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      b[j] = as_bf16x8(*reinterpret_cast<const u32x4*>(base + b_base + j * 4096 + frag_off[kk]));
+  };
+  // The 32 MFMAs of one step.  `mid` runs between the second and the third group of eight: the place where
+  // the next step's slices are written to the other LDS buffer, so that neither the load latency nor the LDS
+  // writes stall the matrix cores.
+  auto multiply = [&](int buf, auto&& mid) {
+    const unsigned char* base = lds + buf * kLmStageBytes;
+    bf16x8 a[2][4], b[2][2];
+    read_frags(base, 0, a[0], b[0]);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      if (kk < 3) read_frags(base, kk + 1, a[(kk + 1) & 1], b[(kk + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk & 1][i], b[kk & 1][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (kk == 1) {
+        mid();
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  };
+
+  LmSoftmax sm;
+  sm.init(it, n_rows, vocab, token_ids, valid);
+
   // ---- main loop over (vocabulary tile, d_model step), flattened so that the prefetch crosses tiles
   const int n_ksteps = (d_model + kLmTileK - 1) / kLmTileK;
-  int vt = vt0, kt = 0, buf = 0;
+  int vt = it.vt0, kt = 0, buf = 0;
   point_w(vt);
   fetch(0);
-  clear_acc();
+  stage(0);
+  __syncthreads();
   for (;;) {
-    stage(buf);
-    __syncthreads();
     int nkt = kt + 1, nvt = vt;
     if (nkt == n_ksteps) { nkt = 0; nvt = vt + 1; }
-    const bool more = nvt < vt1;
+    const bool more = nvt < it.vt1;
     if (more) {
       if (nkt == 0) point_w(nvt);
       fetch(nkt * kLmTileK);
     }
-    multiply(buf);
+    multiply(buf, [&]() { if (more) stage(buf ^ 1); });
     if (kt == n_ksteps - 1) {
-      fold_tile(vt);
-      clear_acc();
+      sm.fold(acc, it, vt, vocab, scale, zy_out);
+      lm_clear(acc);
     }
     if (!more) break;
+    // one barrier per step: the other buffer is complete, and everyone has finished reading this one
+    // before the next step's `mid` overwrites it
+    __syncthreads();
     kt = nkt;
     vt = nvt;
     buf ^= 1;
   }
-
-  // ---- merge the two lane halves, then the two wavefronts along the vocabulary, and emit the partial
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const float om = __shfl_xor(run_m[j], 32), os = __shfl_xor(run_s[j], 32);
-    const float m = fmaxf(run_m[j], om);
-    run_s[j] = run_s[j] * exp2_fast(run_m[j] - m) + os * exp2_fast(om - m);
-    run_m[j] = m;
-  }
-  __syncthreads();                                              // everyone is done with the staging buffers
-  float* xm = reinterpret_cast<float*>(lds);                    // [4 token groups][64 tokens] max, then sum
-  float* xs = xm + 256;
-  if (wv == 1 && half == 0) {
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      xm[wt * 64 + j * 32 + col] = run_m[j];
-      xs[wt * 64 + j * 32 + col] = run_s[j];
-    }
-  }
-  __syncthreads();
-  if (wv == 0 && half == 0) {
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const float om = xm[wt * 64 + j * 32 + col], os = xs[wt * 64 + j * 32 + col];
-      const float m = fmaxf(run_m[j], om);
-      const float s = run_s[j] * exp2_fast(run_m[j] - m) + os * exp2_fast(om - m);
-      if (tok[j] < n_rows) {
-        part_m[(long long)ch * n_rows + tok[j]] = m;
-        part_s[(long long)ch * n_rows + tok[j]] = s;
-      }
-    }
-  }
+  sm.finish(it, reinterpret_cast<float*>(lds), n_rows, part_m, part_s);
 }
 
 // lse and log-prob from the per-chunk partials.  One thread per token.
@@ -336,16 +582,21 @@ LmHeadPlan lm_head_plan(long long n_rows, int vocab, int n_cus) {
   return p;
 }
 
+#ifndef AIS_LM_STAGES
+#define AIS_LM_STAGES 4
+#endif
+
 int launch_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long ld_h, const void* weight, long long ld_w,
                            long long n_rows, int d_model, int vocab, const int* token_ids,
                            const unsigned char* valid, float inv_temperature, const LmHeadPlan& plan,
                            float* part_m, float* part_s, float* zy, float* logp_out, float* lse_out) {
+  constexpr int kStreamLds = AIS_LM_STAGES * kStStageBytes;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_partial_kernel<false>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLmLdsBytes);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_stream_kernel<AIS_LM_STAGES>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kStreamLds);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_partial_kernel<true>),
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_staged_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kLmLdsBytes);
     if (e != hipSuccess) return hip_fail(ctx, e);
     attr_set = true;
@@ -354,8 +605,9 @@ int launch_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long ld_h, con
   const int grid = ((n_items + 7) / 8) * 8;
   {
     ScopedTimer timer(ctx, AIS_K_LM_HEAD);
-    auto kernel = (d_model % kLmTileK != 0) ? lm_head_partial_kernel<true> : lm_head_partial_kernel<false>;
-    kernel<<<grid, kLmThreads, kLmLdsBytes, ctx->stream>>>(
+    const bool stream = d_model % kStK == 0;
+    auto kernel = stream ? lm_head_stream_kernel<AIS_LM_STAGES> : lm_head_staged_kernel;
+    kernel<<<grid, kLmThreads, stream ? kStreamLds : kLmLdsBytes, ctx->stream>>>(
         static_cast<const bf16_t*>(hidden), ld_h, static_cast<const bf16_t*>(weight), ld_w, (int)n_rows, d_model,
         vocab, token_ids, valid, inv_temperature * kLog2e, n_items, plan.n_chunks, plan.tiles_per_chunk,
         plan.n_vtiles, part_m, part_s, zy);

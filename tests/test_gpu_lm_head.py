@@ -66,10 +66,13 @@ def make(R, D, V, seed, p_valid=1.0, scale=1.0, device="cuda"):
     return hidden, weight, y, valid
 
 
-# several tiles in both directions, ragged tails in rows, vocabulary and d_model, and the degenerate sizes
+# several tiles in both directions, ragged tails in rows, vocabulary and d_model, and the degenerate sizes.
+# d_model a multiple of 32 takes the streaming kernel (32: a single step per tile, fewer steps than LDS stages),
+# any other multiple of 8 the register-staged one.
 SHAPES = [
-    (1, 8, 1), (1, 64, 1000), (3, 8, 2), (256, 64, 256), (257, 64, 257), (300, 72, 1000), (513, 128, 2049),
-    (1000, 200, 700), (640, 512, 5000), (255, 64, 70_000),
+    (1, 8, 1), (1, 64, 1000), (3, 8, 2), (5, 32, 100), (256, 64, 256), (257, 64, 257), (300, 72, 1000),
+    (64, 40, 300), (300, 96, 600), (513, 128, 2049), (1000, 200, 700), (640, 512, 5000), (255, 64, 70_000),
+    (700, 32, 1300),
 ]
 
 
