@@ -253,13 +253,14 @@ int ais_fp8_rollout_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, l
  *   logp_out[n] = inv_temperature * z[n, y_n] - lse_n,  lse_n = log sum_v exp(inv_temperature * z[n, v])
  * The [n_rows, vocab] logits are folded into a running (max, sum) per token as they are produced and
  * are never written to memory.
- *   hidden      [n_rows, hidden_stride] device, bf16; the first d_model entries of each row are read
- *               (all rows are read, also those with valid == 0)
+ *   hidden      [n_rows, hidden_stride] device, bf16; the first d_model entries of each row are read;
+ *               rows with valid == 0 are neither read nor evaluated (the evaluated rows are gathered
+ *               into blocks of 256, so the cost follows their number)
  *   weight      [vocab, weight_stride]  device, bf16; row v is the output embedding of token v
  *   token_ids   [n_rows] device; ignored where valid == 0
  *   logp_out, lse_out  [n_rows] device fp32; 0 where valid == 0; a row whose token id is outside
  *               [0, vocab) gets logp 0, its lse, and AIS_STATUS_BAD_TOKEN in the status word
- * Uses the context workspace (2 * chunks + 1 floats per row, chunks <= 64); nothing is retained.
+ * Uses the context workspace (2 * chunks + 3 words per row, chunks <= 64); nothing is retained.
  * Errors: dtype other than AIS_BF16 (AIS_ERR_DTYPE); n_rows < 0, vocab < 1, d_model < 8 or not a
  * multiple of 8 (AIS_ERR_SIZE); a stride < d_model (AIS_ERR_STRIDE); NULL pointers; hidden or weight
  * not 16-byte aligned or a stride not a multiple of 8 elements (AIS_ERR_ALIGN); inv_temperature

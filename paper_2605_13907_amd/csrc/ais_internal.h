@@ -37,12 +37,14 @@ struct WorkspaceLayout {
 };
 WorkspaceLayout workspace_layout(long long n_rows, int n_resp);
 
-// Decomposition of the hidden-state read-out: token blocks x chunks of vocabulary tiles.
+// Decomposition of the hidden-state read-out when every row is evaluated: token blocks x chunks of vocabulary
+// tiles.  The decomposition actually used is decided on the device from the number of evaluated rows.
 struct LmHeadPlan {
   int n_tblocks;        // blocks of 256 tokens
   int n_vtiles;         // tiles of 256 vocabulary entries
   int n_chunks;         // contiguous chunks the tiles are split into
   int tiles_per_chunk;  // tiles of every chunk but possibly the last
+  int max_chunks;       // most chunks the device-side decision can use (sizes the workspace)
 };
 LmHeadPlan lm_head_plan(long long n_rows, int vocab, int n_cus);
 
@@ -110,6 +112,7 @@ int launch_fp8_rollout_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype
 int launch_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long ld_h, const void* weight, long long ld_w,
                            long long n_rows, int d_model, int vocab, const int* token_ids,
                            const unsigned char* valid, float inv_temperature, const LmHeadPlan& plan,
-                           float* part_m, float* part_s, float* zy, float* logp_out, float* lse_out);
+                           float* part_m, float* part_s, float* zy, int* row_index, int* row_pos, void* dev_plan,
+                           float* logp_out, float* lse_out);
 
 }  // namespace ais

@@ -392,15 +392,20 @@ int ais_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long hidden_strid
   if (n_rows == 0) return AIS_OK;
   DeviceGuard guard(ctx->device);
   const LmHeadPlan plan = lm_head_plan(n_rows, (int)vocab, ctx->n_cus);
-  // workspace: per-chunk partial (max, sum) of every token, and the sampled token's logit
+  // workspace: per-chunk partial (max, sum) and the sampled token's logit of every evaluated position, the list
+  // of evaluated rows, its inverse, and the device-side decomposition
   const size_t per = sizeof(float) * (size_t)n_rows;
-  int rc = ensure_workspace(ctx, per * (2 * (size_t)plan.n_chunks + 1));
+  int rc = ensure_workspace(ctx, per * (2 * (size_t)plan.max_chunks + 3) + 256);
   if (rc != AIS_OK) return rc;
   float* part_m = static_cast<float*>(ctx->ws);
-  float* part_s = part_m + (size_t)plan.n_chunks * (size_t)n_rows;
-  float* zy = part_s + (size_t)plan.n_chunks * (size_t)n_rows;
+  float* part_s = part_m + (size_t)plan.max_chunks * (size_t)n_rows;
+  float* zy = part_s + (size_t)plan.max_chunks * (size_t)n_rows;
+  int* row_index = reinterpret_cast<int*>(zy + n_rows);
+  int* row_pos = row_index + n_rows;
+  void* dev_plan = row_pos + n_rows;
   return launch_lm_head_logprob(ctx, hidden, hidden_stride, weight, weight_stride, n_rows, (int)d_model, (int)vocab,
-                                token_ids, valid, inv_temperature, plan, part_m, part_s, zy, logp_out, lse_out);
+                                token_ids, valid, inv_temperature, plan, part_m, part_s, zy, row_index, row_pos,
+                                dev_plan, logp_out, lse_out);
 }
 
 int ais_profile(ais_ctx* ctx, int enable) {

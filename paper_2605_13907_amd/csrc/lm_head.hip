@@ -52,15 +52,64 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 q) { return __builtin_bit_cast
 
 // ---- pieces shared by the two kernels ---------------------------------------------------------------------
 
+// Decomposition of the evaluated rows into work items, decided on the device once their number is known
+// (lm_head_setup_kernel): n_tblocks blocks of 256 evaluated rows x n_chunks chunks of tiles_per_chunk
+// vocabulary tiles, per_xcd work items for each of the 8 XCDs.
+struct LmDevPlan {
+  int n_eval, n_tblocks, n_chunks, tiles_per_chunk, per_xcd, n_items;
+};
+
+// Splits n_vtiles vocabulary tiles into equal chunks so that (token blocks x chunks) equal work items fill the
+// compute units in as few rounds as possible.  Workgroups are bound to XCDs by their index, so what counts is
+// the rounds of the busiest XCD (n_cus / 8 units each).  At most max_items items, at most 64 chunks.
+__host__ __device__ inline void lm_choose_chunks(int n_tblocks, int n_vtiles, int n_cus, long long max_items,
+                                                 int* n_chunks, int* tiles_per_chunk) {
+  const int cus_per_xcd = n_cus >= 8 ? n_cus / 8 : 1;
+  long long best = -1;
+  *n_chunks = 1;
+  *tiles_per_chunk = n_vtiles;
+  for (int chunks = 1; chunks <= n_vtiles && chunks <= 64; ++chunks) {
+    const int tpc = (n_vtiles + chunks - 1) / chunks;
+    const int real = (n_vtiles + tpc - 1) / tpc;
+    const long long items = (long long)n_tblocks * real;
+    if (items > max_items && chunks > 1) continue;
+    const long long per_xcd = (items + 7) / 8;
+    const long long rounds = (per_xcd + cus_per_xcd - 1) / cus_per_xcd;
+    const long long cost = rounds * (tpc + 1);            // + 1: set-up and tear-down of a work item, in tile units
+    if (best < 0 || cost < best) {
+      best = cost;
+      *tiles_per_chunk = tpc;
+      *n_chunks = real;
+    }
+  }
+}
+
+// The rows to evaluate.  With a mask, `index` lists the evaluated rows in order (built by
+// lm_head_setup_kernel); without one, every row is evaluated.
+struct LmRows {
+  const int* index;
+  int n_rows;
+  // source row of evaluated position p (positions past the end repeat the last one; their results are discarded)
+  __device__ __forceinline__ int row(int p, int n_eval) const {
+    p = min(p, n_eval - 1);
+    return index != nullptr ? index[p] : p;
+  }
+};
+
 // Which part of the problem this workgroup owns, and where the thread sits in its tile.
 struct LmItem {
-  int tb, ch, vt0, vt1, t0;
+  int tb, ch, vt0, vt1, t0, n_eval, n_chunks;
   int lane, wave, wv, wt, half, col;
-  __device__ __forceinline__ bool init(int n_items, int n_chunks, int tiles_per_chunk, int n_vtiles) {
-    // Workgroups are dealt to the 8 XCDs round-robin; give every XCD a contiguous range of work items.
-    const int per_xcd = gridDim.x >> 3;
-    const int item = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-    if (item >= n_items) return false;                           // uniform for the workgroup
+  __device__ __forceinline__ bool init(const LmDevPlan* __restrict__ plan, int n_vtiles) {
+    // Workgroups are dealt to the 8 XCDs round-robin; every XCD takes a contiguous, equally long range of work
+    // items (token block major): its resident workgroups then share a few token blocks' hidden-state slices and
+    // each other's vocabulary tiles through the L2.
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int item = xcd * plan->per_xcd + local;
+    if (local >= plan->per_xcd || item >= plan->n_items) return false;   // uniform for the workgroup
+    n_eval = plan->n_eval;
+    n_chunks = plan->n_chunks;
+    const int tiles_per_chunk = plan->tiles_per_chunk;
     tb = item / n_chunks;
     ch = item - tb * n_chunks;
     vt0 = ch * tiles_per_chunk;
@@ -91,16 +140,17 @@ __device__ __forceinline__ void lm_clear(LmAcc& acc) {
 struct LmSoftmax {
   float run_m[2], run_s[2];
   int tok[2], y[2];
-  __device__ __forceinline__ void init(const LmItem& it, int n_rows, int vocab, const int* __restrict__ token_ids,
-                                       const unsigned char* __restrict__ valid) {
+  // tok[j]: evaluated position of the lane's token column j; y[j]: its sampled token, -1 if there is none to find
+  __device__ __forceinline__ void init(const LmItem& it, const LmRows& rows, int vocab,
+                                       const int* __restrict__ token_ids) {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       run_m[j] = kNegHuge;
       run_s[j] = 0.f;
       tok[j] = it.t0 + it.wt * kLmWaveT + j * 32 + it.col;
       y[j] = -1;
-      if (tok[j] < n_rows && (valid == nullptr || valid[tok[j]] != 0)) {
-        const int id = token_ids[tok[j]];
+      if (tok[j] < it.n_eval) {
+        const int id = token_ids[rows.row(tok[j], it.n_eval)];
         y[j] = (id >= 0 && id < vocab) ? id : -1;
       }
     }
@@ -180,7 +230,7 @@ struct LmSoftmax {
         const float om = xm[it.wt * 64 + j * 32 + it.col], os = xs[it.wt * 64 + j * 32 + it.col];
         const float m = fmaxf(run_m[j], om);
         const float s = run_s[j] * exp2_fast(run_m[j] - m) + os * exp2_fast(om - m);
-        if (tok[j] < n_rows) {
+        if (tok[j] < it.n_eval) {
           part_m[(long long)it.ch * n_rows + tok[j]] = m;
           part_s[(long long)it.ch * n_rows + tok[j]] = s;
         }
@@ -213,12 +263,13 @@ __device__ __forceinline__ int st_chunk_offset(int row, int c) { return row * 64
 template <int NS>
 __global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(
     const bf16_t* __restrict__ hidden, long long ld_h, const bf16_t* __restrict__ weight, long long ld_w,
-    int n_rows, int d_model, int vocab, const int* __restrict__ token_ids, const unsigned char* __restrict__ valid,
-    float scale, int n_items, int n_chunks, int tiles_per_chunk, int n_vtiles, float* __restrict__ part_m,
-    float* __restrict__ part_s, float* __restrict__ zy_out) {
+    LmRows rows, const LmDevPlan* __restrict__ plan, int d_model, int vocab, const int* __restrict__ token_ids,
+    float scale, int n_vtiles, float* __restrict__ part_m, float* __restrict__ part_s,
+    float* __restrict__ zy_out) {
   extern __shared__ __align__(16) unsigned char lds[];
   LmItem it;
-  if (!it.init(n_items, n_chunks, tiles_per_chunk, n_vtiles)) return;
+  if (!it.init(plan, n_vtiles)) return;
+  const int n_rows = rows.n_rows;
   const int lane = it.lane, wave = it.wave;
 
   // ---- copies: wavefront w moves rows 16 w .. 16 w + 15 (+ 128 j) of each slice; a lane sits at chunk position
@@ -229,7 +280,7 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(
   const bf16_t* wp[2];
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
-    const int trow = min(it.t0 + crow + 128 * j, n_rows - 1);   // rows past the end repeat the last one; discarded later
+    const int trow = rows.row(it.t0 + crow + 128 * j, it.n_eval);
     hp[j] = hidden + (long long)trow * ld_h + cchunk * 8;
   }
   auto point_w = [&](int vt) {
@@ -301,7 +352,7 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
   };
   LmSoftmax sm;
-  sm.init(it, n_rows, vocab, token_ids, valid);
+  sm.init(it, rows, vocab, token_ids);
 
   // Every wavefront issues 4 copies per step and they complete in order: waiting until at most 4 * younger
   // are outstanding means the step before the `younger` most recent ones has landed.
@@ -399,12 +450,13 @@ __device__ __forceinline__ int lds_chunk_offset(int row, int c) { return row * 1
 
 __global__ __launch_bounds__(kLmThreads) void lm_head_staged_kernel(
     const bf16_t* __restrict__ hidden, long long ld_h, const bf16_t* __restrict__ weight, long long ld_w,
-    int n_rows, int d_model, int vocab, const int* __restrict__ token_ids, const unsigned char* __restrict__ valid,
-    float scale, int n_items, int n_chunks, int tiles_per_chunk, int n_vtiles, float* __restrict__ part_m,
-    float* __restrict__ part_s, float* __restrict__ zy_out) {
+    LmRows rows, const LmDevPlan* __restrict__ plan, int d_model, int vocab, const int* __restrict__ token_ids,
+    float scale, int n_vtiles, float* __restrict__ part_m, float* __restrict__ part_s,
+    float* __restrict__ zy_out) {
   extern __shared__ __align__(16) unsigned char lds[];
   LmItem it;
-  if (!it.init(n_items, n_chunks, tiles_per_chunk, n_vtiles)) return;
+  if (!it.init(plan, n_vtiles)) return;
+  const int n_rows = rows.n_rows;
   const int tid = threadIdx.x;
 
   // ---- global -> registers -> LDS: thread owns chunk c of rows r0 + 64 i of both operand slices
@@ -413,7 +465,7 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_staged_kernel(
   const bf16_t* wp[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int trow = min(it.t0 + r0 + 64 * i, n_rows - 1);      // rows past the end repeat the last one; discarded later
+    const int trow = rows.row(it.t0 + r0 + 64 * i, it.n_eval);
     hp[i] = hidden + (long long)trow * ld_h + c * 8;
   }
   auto point_w = [&](int vt) {
@@ -492,7 +544,7 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_staged_kernel(
   };
 
   LmSoftmax sm;
-  sm.init(it, n_rows, vocab, token_ids, valid);
+  sm.init(it, rows, vocab, token_ids);
 
   // ---- main loop over (vocabulary tile, d_model step), flattened so that the prefetch crosses tiles
   const int n_ksteps = (d_model + kLmTileK - 1) / kLmTileK;
@@ -525,31 +577,84 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_staged_kernel(
   sm.finish(it, reinterpret_cast<float*>(lds), n_rows, part_m, part_s);
 }
 
-// lse and log-prob from the per-chunk partials.  One thread per token.
+// One workgroup, before the main kernel.  With a mask it lists the rows to evaluate (index[p] = p-th row with
+// valid != 0, pos[n] = position of row n in that list or -1; each thread owns a contiguous run of rows); in
+// both cases thread 0 then decides the decomposition for the number of evaluated rows.
+__global__ __launch_bounds__(1024) void lm_head_setup_kernel(const unsigned char* __restrict__ valid, int n_rows,
+                                                             int n_vtiles, int n_cus, int max_items,
+                                                             int* __restrict__ index, int* __restrict__ pos,
+                                                             LmDevPlan* __restrict__ plan) {
+  __shared__ int run_start[1024];
+  __shared__ int total;
+  const int tid = threadIdx.x;
+  if (valid != nullptr) {
+    const int per = (n_rows + 1023) / 1024;
+    const int r0 = min(n_rows, tid * per), r1 = min(n_rows, r0 + per);
+    int cnt = 0;
+    for (int n = r0; n < r1; ++n) cnt += valid[n] != 0;
+    run_start[tid] = cnt;
+    __syncthreads();
+    if (tid == 0) {
+      int run = 0;
+      for (int t = 0; t < 1024; ++t) {
+        const int c = run_start[t];
+        run_start[t] = run;
+        run += c;
+      }
+      total = run;
+    }
+    __syncthreads();
+    int p = run_start[tid];
+    for (int n = r0; n < r1; ++n) {
+      if (valid[n] != 0) {
+        index[p] = n;
+        pos[n] = p++;
+      } else {
+        pos[n] = -1;
+      }
+    }
+  } else if (tid == 0) {
+    total = n_rows;
+  }
+  if (tid == 0) {
+    LmDevPlan d;
+    d.n_eval = total;
+    d.n_tblocks = (total + kLmTileT - 1) / kLmTileT;
+    lm_choose_chunks(d.n_tblocks, n_vtiles, n_cus, max_items, &d.n_chunks, &d.tiles_per_chunk);
+    d.n_items = d.n_tblocks * d.n_chunks;
+    d.per_xcd = (d.n_items + 7) / 8;
+    *plan = d;
+  }
+}
+
+// lse and log-prob from the per-chunk partials.  One thread per row; partials are stored by evaluated position.
 __global__ __launch_bounds__(256) void lm_head_merge_kernel(const float* __restrict__ part_m,
                                                             const float* __restrict__ part_s,
-                                                            const float* __restrict__ zy, int n_rows, int n_chunks,
-                                                            int vocab, const int* __restrict__ token_ids,
-                                                            const unsigned char* __restrict__ valid,
+                                                            const float* __restrict__ zy, int n_rows,
+                                                            const LmDevPlan* __restrict__ plan, int vocab,
+                                                            const int* __restrict__ token_ids,
+                                                            const int* __restrict__ pos,
                                                             float inv_temperature, float* __restrict__ logp_out,
                                                             float* __restrict__ lse_out, int* __restrict__ status) {
   const int n = blockIdx.x * 256 + threadIdx.x;
   if (n >= n_rows) return;
-  if (valid != nullptr && valid[n] == 0) {
+  const int n_chunks = plan->n_chunks;
+  const int p = pos != nullptr ? pos[n] : n;
+  if (p < 0) {
     logp_out[n] = 0.f;
     lse_out[n] = 0.f;
     return;
   }
   float m = kNegHuge;
-  for (int k = 0; k < n_chunks; ++k) m = fmaxf(m, part_m[(long long)k * n_rows + n]);
+  for (int k = 0; k < n_chunks; ++k) m = fmaxf(m, part_m[(long long)k * n_rows + p]);
   double s = 0.0;
   for (int k = 0; k < n_chunks; ++k)
-    s += (double)part_s[(long long)k * n_rows + n] * (double)exp2_fast(part_m[(long long)k * n_rows + n] - m);
+    s += (double)part_s[(long long)k * n_rows + p] * (double)exp2_fast(part_m[(long long)k * n_rows + p] - m);
   const double lse = ((double)m + log2(s)) * 0.6931471805599453;
   lse_out[n] = (float)lse;
   const int id = token_ids[n];
   if (id >= 0 && id < vocab) {
-    logp_out[n] = (float)((double)zy[n] * (double)inv_temperature - lse);
+    logp_out[n] = (float)((double)zy[p] * (double)inv_temperature - lse);
   } else {
     logp_out[n] = 0.f;
     atomicOr(status, AIS_STATUS_BAD_TOKEN);
@@ -558,27 +663,13 @@ __global__ __launch_bounds__(256) void lm_head_merge_kernel(const float* __restr
 
 }  // namespace
 
-// Splits the vocabulary tiles into equal chunks so that (token blocks x chunks) work items of equal size
-// fill the compute units in as few rounds as possible.
+// Worst case of the decomposition (every row evaluated): sizes the grid and the workspace.
 LmHeadPlan lm_head_plan(long long n_rows, int vocab, int n_cus) {
   LmHeadPlan p;
   p.n_tblocks = (int)((n_rows + kLmTileT - 1) / kLmTileT);
   p.n_vtiles = (vocab + kLmTileV - 1) / kLmTileV;
-  long long best = -1;
-  p.tiles_per_chunk = p.n_vtiles;
-  p.n_chunks = 1;
-  for (int chunks = 1; chunks <= p.n_vtiles && chunks <= 64; ++chunks) {
-    const int tpc = (p.n_vtiles + chunks - 1) / chunks;
-    const int real = (p.n_vtiles + tpc - 1) / tpc;
-    const long long items = (long long)p.n_tblocks * real;
-    const long long rounds = (items + n_cus - 1) / n_cus;
-    const long long cost = rounds * (tpc + 1);            // + 1: set-up and tear-down of a work item, in tile units
-    if (best < 0 || cost < best) {
-      best = cost;
-      p.tiles_per_chunk = tpc;
-      p.n_chunks = real;
-    }
-  }
+  lm_choose_chunks(p.n_tblocks, p.n_vtiles, n_cus, 1LL << 40, &p.n_chunks, &p.tiles_per_chunk);
+  p.max_chunks = p.n_vtiles < 64 ? p.n_vtiles : 64;
   return p;
 }
 
@@ -589,7 +680,8 @@ LmHeadPlan lm_head_plan(long long n_rows, int vocab, int n_cus) {
 int launch_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long ld_h, const void* weight, long long ld_w,
                            long long n_rows, int d_model, int vocab, const int* token_ids,
                            const unsigned char* valid, float inv_temperature, const LmHeadPlan& plan,
-                           float* part_m, float* part_s, float* zy, float* logp_out, float* lse_out) {
+                           float* part_m, float* part_s, float* zy, int* row_index, int* row_pos, void* dev_plan,
+                           float* logp_out, float* lse_out) {
   constexpr int kStreamLds = AIS_LM_STAGES * kStStageBytes;
   static bool attr_set = false;
   if (!attr_set) {
@@ -601,22 +693,28 @@ int launch_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long ld_h, con
     if (e != hipSuccess) return hip_fail(ctx, e);
     attr_set = true;
   }
-  const int n_items = plan.n_tblocks * plan.n_chunks;
-  const int grid = ((n_items + 7) / 8) * 8;
+  // The grid covers the work items of the worst case; with fewer evaluated rows the device-side plan may use
+  // more, shorter chunks, but never more items than that, and the workgroups left over leave at once.
+  const int max_items = ((plan.n_tblocks * plan.n_chunks + 7) / 8) * 8;
+  LmDevPlan* dplan = static_cast<LmDevPlan*>(dev_plan);
+  lm_head_setup_kernel<<<1, 1024, 0, ctx->stream>>>(valid, (int)n_rows, plan.n_vtiles, ctx->n_cus, max_items,
+                                                    row_index, row_pos, dplan);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  LmRows rows{valid != nullptr ? row_index : nullptr, (int)n_rows};
   {
     ScopedTimer timer(ctx, AIS_K_LM_HEAD);
     const bool stream = d_model % kStK == 0;
     auto kernel = stream ? lm_head_stream_kernel<AIS_LM_STAGES> : lm_head_staged_kernel;
-    kernel<<<grid, kLmThreads, stream ? kStreamLds : kLmLdsBytes, ctx->stream>>>(
-        static_cast<const bf16_t*>(hidden), ld_h, static_cast<const bf16_t*>(weight), ld_w, (int)n_rows, d_model,
-        vocab, token_ids, valid, inv_temperature * kLog2e, n_items, plan.n_chunks, plan.tiles_per_chunk,
-        plan.n_vtiles, part_m, part_s, zy);
+    kernel<<<max_items, kLmThreads, stream ? kStreamLds : kLmLdsBytes, ctx->stream>>>(
+        static_cast<const bf16_t*>(hidden), ld_h, static_cast<const bf16_t*>(weight), ld_w, rows, dplan, d_model,
+        vocab, token_ids, inv_temperature * kLog2e, plan.n_vtiles, part_m, part_s, zy);
   }
-  hipError_t e = hipGetLastError();
+  e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(ctx, e);
   lm_head_merge_kernel<<<(unsigned)((n_rows + 255) / 256), 256, 0, ctx->stream>>>(
-      part_m, part_s, zy, (int)n_rows, plan.n_chunks, vocab, token_ids, valid, inv_temperature, logp_out, lse_out,
-      ctx->status_dev);
+      part_m, part_s, zy, (int)n_rows, dplan, vocab, token_ids, valid != nullptr ? row_pos : nullptr,
+      inv_temperature, logp_out, lse_out, ctx->status_dev);
   return hip_fail(ctx, hipGetLastError());
 }
 

@@ -121,6 +121,22 @@ def test_bad_tokens_and_masked_rows(ctx):
     assert ctx.status() == 0                                      # reading the status cleared it
 
 
+@pytest.mark.parametrize("p_valid", [0.03, 0.3, 0.97])
+def test_masked_rows_are_gathered(ctx, p_valid):
+    """Only evaluated rows are read and computed: every other row holds NaN, the first and last rows are masked,
+    and the evaluated rows straddle several token blocks."""
+    hidden, weight, y, _ = make(3000, 128, 2000, seed=21)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(22)
+    valid = (torch.rand(3000, generator=g) < p_valid).to(torch.uint8)
+    valid[0] = valid[-1] = 0
+    valid[1500] = 1
+    valid = valid.cuda()
+    hidden[valid == 0] = float("nan")
+    y = torch.where(valid.bool(), y, torch.full_like(y, -1))
+    compare(ctx, hidden, weight, y, valid)
+
+
 def test_all_rows_masked(ctx):
     hidden, weight, y, _ = make(70, 64, 300, seed=15)
     valid = torch.zeros(70, dtype=torch.uint8, device="cuda")
@@ -146,6 +162,17 @@ def test_reproducible(ctx):
 def test_workload_1(ctx):
     batch = W.generate_readout(W.config(1), device="cuda")
     compare(ctx, batch.hidden, batch.weight, batch.token_ids, batch.valid)
+
+
+def test_workload_3_masked_full_vocab(ctx):
+    """The masked-diffusion workload (about half of the positions evaluated) at its full vocabulary and model width,
+    on a slice of its rows; the oracle evaluates a sample."""
+    shape = W.config(3)
+    batch = W.generate_readout(shape, device="cuda", n_rows=6000)
+    v = batch.valid.cpu().numpy().astype(bool)
+    rng = np.random.default_rng(6)
+    rows = np.unique(np.concatenate([np.flatnonzero(v)[[0, 1, 255, 256, -1]], rng.integers(0, 6000, 30)]))
+    compare(ctx, batch.hidden, batch.weight, batch.token_ids, batch.valid, rows=rows)
 
 
 def test_full_size_sampled(ctx):
