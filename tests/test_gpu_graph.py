@@ -48,3 +48,36 @@ def test_graph_replays_match_eager():
             assert torch.equal(a, b), f"replay {it}: {name} differs from the eager result"
     assert ctx.status() == 0
     ctx.close()
+
+
+def test_lm_head_graph_replays_match_eager():
+    """The hidden-state log-prob call under capture: its set-up kernel decides the decomposition on the device, so
+    a replay with a different mask (a different number of evaluated rows) must still match the eager result."""
+    ctx = B.AisContext()
+    g = torch.Generator(device="cpu")
+    g.manual_seed(31)
+    R, D, V = 1500, 128, 3000
+    hidden = torch.randn(R, D, generator=g).to(torch.bfloat16).cuda()
+    weight = (torch.randn(V, D, generator=g) / D ** 0.5 * 3).to(torch.bfloat16).cuda()
+    y = torch.randint(0, V, (R,), generator=g, dtype=torch.int32).cuda()
+    valid = (torch.rand(R, generator=g) < 0.6).to(torch.uint8).cuda()
+    ctx.lm_head_logprob(hidden, weight, y, valid)          # warm-up: sizes the workspace outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            g_logp, g_lse = ctx.lm_head_logprob(hidden, weight, y, valid)
+    torch.cuda.synchronize()
+    for it, p_valid in enumerate((0.6, 0.05, 1.0, 0.3)):
+        valid.copy_((torch.rand(R, generator=g) < p_valid).to(torch.uint8))
+        hidden.mul_(1.0 + 0.1 * it)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (g_logp.clone(), g_lse.clone())
+        ref = ctx.lm_head_logprob(hidden, weight, y, valid)
+        torch.cuda.synchronize()
+        assert torch.equal(got[0], ref[0]) and torch.equal(got[1], ref[1]), f"replay {it} differs from the eager result"
+    assert ctx.status() == 0
+    ctx.close()
