@@ -432,6 +432,8 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(
 #undef AIS_PIN
   mfma_range(a1, b1, 2, 8);
   sm.fold(acc, it, vt, vocab, scale, zy_out);
+  // copies of the last steps may still be in flight, and they land in LDS that finish() is about to reuse
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   sm.finish(it, reinterpret_cast<float*>(lds), n_rows, part_m, part_s);
 }
 

@@ -175,6 +175,15 @@ def test_workload_3_masked_full_vocab(ctx):
     compare(ctx, batch.hidden, batch.weight, batch.token_ids, batch.valid, rows=rows)
 
 
+def test_workload_4_widest_vocabulary(ctx):
+    """The widest vocabulary of the workloads (248,320 = 970 tiles) on 1,024 of its rows: few token blocks, so the
+    device-side decomposition uses its largest chunk counts."""
+    batch = W.generate_readout(W.config(4), device="cuda", n_rows=1024)
+    rng = np.random.default_rng(7)
+    rows = np.unique(np.concatenate([[0, 255, 256, 1023], rng.integers(0, 1024, 20)]))
+    compare(ctx, batch.hidden, batch.weight, batch.token_ids, batch.valid, rows=rows)
+
+
 def test_full_size_sampled(ctx):
     """Workload 2 at full size (41,643 rows, d_model 4096, vocabulary 151,936) in the launch configuration the
     benchmark times; the oracle evaluates a sample of rows that covers the first and last token block and the
