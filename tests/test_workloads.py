@@ -125,3 +125,26 @@ def test_sampled_tokens_follow_rollout_softmax():
     freq = torch.bincount(b.token_ids.long(), minlength=4).double() / b.n_rows
     assert float((freq - 0.25).abs().max()) < 0.03
     assert torch.allclose(b.logp_roll, torch.full_like(b.logp_roll, -math.log(4)), atol=1e-6)
+
+
+def test_readout_generator_structure_and_determinism():
+    """Hidden states and output embeddings of the read-out: shapes, dtypes, row structure shared with the rollout
+    batch of the same workload, masked rows without a token, the preferred token dominating sharp rows."""
+    shape = W.config(1)
+    a = W.generate_readout(shape)
+    b = W.generate_readout(shape)
+    assert torch.equal(a.hidden, b.hidden) and torch.equal(a.weight, b.weight) and torch.equal(a.token_ids, b.token_ids)
+    _, valid, _, _ = W.layout_of(shape)
+    assert a.hidden.shape == (valid.numel(), W.D_MODEL["tiny"]) and a.weight.shape == (shape.vocab, W.D_MODEL["tiny"])
+    assert a.hidden.dtype == torch.bfloat16 and a.weight.dtype == torch.bfloat16
+    assert torch.equal(a.valid, valid)
+    assert bool((a.token_ids[valid == 0] == -1).all())
+    tid = a.token_ids[valid != 0]
+    assert int(tid.min()) >= 0 and int(tid.max()) < shape.vocab
+    # rows are neither flat nor all one-hot: the largest probability of a row spreads over (0, 1)
+    z = a.hidden.double() @ a.weight.double().t()
+    pmax = torch.softmax(z, dim=1).max(dim=1).values
+    assert float(pmax.min()) < 0.2 and float(pmax.max()) > 0.9
+    # a slice of the rows is the leading part of the same batch structure
+    c = W.generate_readout(shape, n_rows=100)
+    assert c.hidden.shape[0] == 100 and torch.equal(c.valid, valid[:100])
