@@ -18,6 +18,8 @@ int main(void) {
   if (ais_token_logprob(NULL, fake, AIS_F32, 4, 64, 64, (const int*)fake, NULL, 1.0f, fake, fake) != AIS_ERR_NULL) fails++;
   p.C = 0.5f;
   if (ais_diagnostics(NULL, fake, fake, NULL, 4, cu, 2, 2, fake, &p, fake, (int*)fake, (ais_diag*)fake) != AIS_ERR_PARAM) fails++;
+  if (ais_lm_head_logprob(NULL, fake, 64, fake, 64, AIS_F32, 4, 64, 100, (const int*)fake, NULL, 1.0f, fake, fake) != AIS_ERR_DTYPE) fails++;
+  if (ais_lm_head_logprob(NULL, fake, 64, fake, 64, AIS_BF16, 4, 60, 100, (const int*)fake, NULL, 1.0f, fake, fake) != AIS_ERR_SIZE) fails++;
   if (ais_destroy(NULL) != AIS_OK) fails++;
   if (sizeof(ais_diag) != 136 || sizeof(ais_params) != 40) fails++;
   printf("%d\n", fails);
