@@ -128,3 +128,23 @@ def test_masked_rows_bad_token_and_reproducibility(ctx):
     torch.cuda.synchronize()
     assert ctx.status() & B.STATUS_BAD_TOKEN and out["logp"][first].item() == 0
     assert torch.isfinite(out["sgrad"].float()).all()
+
+
+@pytest.mark.parametrize("vocab", [4_107, 151_936])
+def test_vocabulary_masked_with_minus_infinity(ctx, vocab):
+    """Banned tokens (-inf logits) through the register-resident kernel: probability and direction exactly 0 there,
+    no NaN; whole vectors, the ragged tail and a row that keeps only its sampled token."""
+    shape = W.config(2).scaled(vocab=vocab, len_div=64 if vocab < 10_000 else 256, seed=78)
+    batch = W.generate(shape, "cuda", row_chunk=128)
+    R, V = batch.logits.shape
+    g = torch.Generator(device="cuda")
+    g.manual_seed(6)
+    ban = torch.rand(R, V, generator=g, device="cuda") < 0.33
+    ban[:, V - 11:] = True
+    ban[:, 64:96] = True
+    ban[3] = True
+    ban[torch.arange(R, device="cuda"), batch.token_ids.long().clamp(min=0)] = False
+    batch.logits[ban] = float("-inf")
+    out, ref, d = check_one_sweep(ctx, batch)
+    assert torch.isfinite(out["logp"]).all() and torch.isfinite(out["sgrad"].float()).all()
+    assert bool((out["sgrad"][ban] == 0).all())

@@ -156,6 +156,29 @@ def test_many_short_responses(ctx):
     assert d["n_valid"] == int(batch.valid.sum().item()) and (out["count"] == 0).sum().item() >= 40
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_vocabulary_masked_with_minus_infinity(ctx, dtype):
+    """Logits processors ban tokens by setting their logit to -inf.  A third of every row's vocabulary is banned
+    (never the sampled token), whole 16-byte vectors and the ragged tail included; one row keeps only its sampled
+    token.  Banned entries must get probability 0 and gradient exactly 0, with no NaN anywhere."""
+    shape = dataclasses_replace(W.config(2).scaled(vocab=4_107, len_div=64, seed=77), logits_dtype=dtype)
+    batch = gen(shape)
+    R, V = batch.logits.shape
+    g = torch.Generator(device="cpu")
+    g.manual_seed(5)
+    ban = torch.rand(R, V, generator=g) < 0.33
+    ban[:, 4096:] = True                                   # the tail past the last full vector
+    ban[:, 64:96] = True                                   # whole vectors
+    ban[3] = True                                          # a row with nothing but its sampled token
+    ban = ban.cuda()
+    ban[torch.arange(R, device="cuda"), batch.token_ids.long().clamp(min=0)] = False
+    batch.logits[ban] = float("-inf")
+    out, ref, d = P.check(ctx, batch)
+    assert torch.isfinite(out["logp"]).all() and torch.isfinite(out["dlogits"].float()).all()
+    assert bool((out["dlogits"][ban] == 0).all())
+    assert abs(float(out["logp"][3])) < 1e-6
+
+
 def test_all_ratios_truncated(ctx):
     """rho > C on every token: w_bar == C, CV = 0, alpha_ess = 1, clip_frac = 1."""
     shape = W.config(2).scaled(vocab=1032, len_div=64, seed=21)
