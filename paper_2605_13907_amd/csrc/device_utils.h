@@ -18,6 +18,13 @@ constexpr float kNegHuge = -3.0e38f;   // finite stand-in for -inf: keeps (max -
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float log2_fast(float x) { return __builtin_amdgcn_logf(x); }
 
+// log(1 + s * 2^e) for s >= 0, in fp64, without overflow when e is large (a sampled token thousands of units
+// below the row maximum makes s * 2^e exceed the range of a double, while its logarithm is an ordinary number).
+__device__ __forceinline__ double log1p_scaled(double s, double e) {
+  const double l2 = log2(s) + e;                 // log2 of the ratio; -inf when s == 0
+  return l2 > 64.0 ? l2 * 0.6931471805599453 : log1p(exp2(l2));
+}
+
 __device__ __forceinline__ u32x4 load_stream(const u32x4* p) { return __builtin_nontemporal_load(p); }
 __device__ __forceinline__ void store_stream(u32x4* p, u32x4 v) { __builtin_nontemporal_store(v, p); }
 

@@ -130,8 +130,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
     for (int w = 1; w < kRowWaves; ++w) t = merge(t, lds[w]);
     float lse, logp;
     if (y_ok) {
-      const double r = (double)t.s * exp2((double)t.m - (double)zy * (double)scale);
-      const double l1p = log1p(r);
+      const double l1p = log1p_scaled((double)t.s, (double)t.m - (double)zy * (double)scale);
       logp = (float)(-l1p);
       lse = (float)((double)zy * (double)inv_temperature + l1p);
     } else {

@@ -148,3 +148,12 @@ def test_vocabulary_masked_with_minus_infinity(ctx, vocab):
     out, ref, d = check_one_sweep(ctx, batch)
     assert torch.isfinite(out["logp"]).all() and torch.isfinite(out["sgrad"].float()).all()
     assert bool((out["sgrad"][ban] == 0).all())
+
+
+def test_extreme_logit_magnitudes(ctx):
+    """Logits thousands of units apart through the register-resident kernel: sampled tokens whose probability
+    underflows a double still get a finite log-prob."""
+    batch = W.generate(W.config(2).scaled(vocab=4_104, len_div=64, seed=79), "cuda")
+    batch.logits.mul_(1000.0)
+    out, ref, d = check_one_sweep(ctx, batch)
+    assert torch.isfinite(out["logp"]).all() and float(out["logp"].min()) < -1000.0

@@ -179,6 +179,18 @@ def test_vocabulary_masked_with_minus_infinity(ctx, dtype):
     assert abs(float(out["logp"][3])) < 1e-6
 
 
+@pytest.mark.parametrize("dtype,factor", [("bf16", 1000.0), ("f32", 3000.0)])
+def test_extreme_logit_magnitudes(ctx, dtype, factor):
+    """Logits thousands of units apart: the soft-max is one-hot to working precision, lse is of order 1e4, and
+    nothing may overflow (the running maximum is subtracted before every exponential)."""
+    shape = dataclasses_replace(W.config(2).scaled(vocab=4_104, len_div=64, seed=79), logits_dtype=dtype)
+    batch = gen(shape)
+    batch.logits.mul_(factor)
+    out, ref, d = P.check(ctx, batch)
+    assert torch.isfinite(out["lse"]).all() and float(out["lse"].abs().max()) > 3000.0
+    assert torch.isfinite(out["dlogits"].float()).all()
+
+
 def test_all_ratios_truncated(ctx):
     """rho > C on every token: w_bar == C, CV = 0, alpha_ess = 1, clip_frac = 1."""
     shape = W.config(2).scaled(vocab=1032, len_div=64, seed=21)
