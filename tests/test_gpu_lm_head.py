@@ -91,6 +91,14 @@ def test_temperature_and_peaked_rows(ctx, inv_t):
     compare(ctx, hidden, weight, y, valid, inv_t)
 
 
+def test_large_logits(ctx):
+    """Hidden states a hundred times larger: logits hundreds of units apart, sampled tokens with probabilities far
+    below fp32 range; the running maximum keeps every exponential in range and the log-prob stays finite."""
+    hidden, weight, y, valid = make(300, 128, 3000, seed=18, scale=100.0)
+    logp, lse = compare(ctx, hidden, weight, y, valid)
+    assert torch.isfinite(logp).all() and float(logp.min()) < -200.0
+
+
 def test_deep_contraction(ctx):
     """d_model = 4096: the accumulation length of the real workloads."""
     hidden, weight, y, valid = make(512, 4096, 4096, seed=12, p_valid=0.9)
