@@ -11,8 +11,10 @@
 // A 151,936-wide bf16 row is 297 KiB; a CDNA4 compute unit has 512 KiB of vector registers.  One
 // workgroup of 1,024 threads (16 wavefronts, 4 per SIMD, up to 128 registers per lane) holds the row as
 // NV 16-byte vectors per lane.  All NV loads of a lane are issued back to back, so the whole row is in
-// flight at once and memory latency is paid once per row.  Rows too wide for the register file fall back
-// to the two-pass kernels.
+// flight at once and memory latency is paid once per row.  Rows wider than 24 vectors per lane keep their
+// last 9 vectors per lane in LDS (144 KiB of the compute unit's 160), which are filled by direct
+// global -> LDS copies and never pass through registers on the way in: up to 31 vectors per lane, 253,952
+// bf16 elements.  Rows wider than that fall back to the two-pass kernels.
 #include "ais_internal.h"
 #include "device_utils.h"
 
@@ -49,8 +51,13 @@ template <> __device__ __forceinline__ u32x4 patch_lowest<float>(u32x4 q, int su
   return q;
 }
 
-// grid.x = n_rows, block = kRowThreads.  Requires 16-byte aligned rows and vocab / N <= NV * kRowThreads.
-template <typename T, int NV>
+typedef __attribute__((address_space(3))) void* lds_ptr;
+typedef const __attribute__((address_space(1))) void* glb_ptr;
+
+// grid.x = n_rows, block = kRowThreads.  Requires 16-byte aligned rows and vocab / N <= (NV + NL) * kRowThreads.
+// Vector k of a lane (elements N * (tid + 1024 k) ..) lives in register q[k] for k < NV and in LDS slot k - NV
+// (16 bytes at byte offset 16 * (1024 (k - NV) + tid) of the dynamic LDS) for NV <= k < NV + NL.
+template <typename T, int NV, int NL>
 __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
     const T* logits, long long row_stride, int vocab, const int* __restrict__ token_ids,
     const unsigned char* __restrict__ valid, float inv_temperature, float* __restrict__ logp_out,
@@ -58,6 +65,8 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
   constexpr int N = Vec<T>::N;
   __shared__ MaxSum lds[kRowWaves];
   __shared__ float lds_row[2];          // shift (= -lse * log2e) and the sampled token's element
+  extern __shared__ __align__(16) unsigned char lds_slots[];
+  u32x4* lrow = reinterpret_cast<u32x4*>(lds_slots);
   const long long row = blockIdx.x;
   const int tid = threadIdx.x;
   const T* zr = logits + row * row_stride;
@@ -73,7 +82,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
     }
     const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int k = 0; k < NV; ++k) {
+    for (int k = 0; k < NV + NL; ++k) {
       const int i = tid + k * kRowThreads;
       if (i < nvec) store_stream(sv + i, zero);
     }
@@ -88,6 +97,19 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
   for (int k = 0; k < NV; ++k) {
     const int i = tid + k * kRowThreads;
     q[k] = (i < nvec) ? load_stream(zv + i) : lowest_fill<T>();
+  }
+  // the LDS slots: lane i of a wavefront deposits its 16 bytes at the wavefront's base + 16 i, which is the
+  // slot layout; lanes past the end of the row re-read its last vector (a valid address) and are masked later
+  if (NL > 0) {
+    int tid0 = tid;                                   // opaque copies keep the per-vector offsets short-lived
+    asm volatile("" : "+v"(tid0));
+#pragma unroll
+    for (int k = 0; k < NL; ++k) {
+      const int i = min(tid0 + (NV + k) * kRowThreads, nvec - 1);
+      __builtin_amdgcn_global_load_lds((glb_ptr)(zv + i), (lds_ptr)(lrow + k * kRowThreads + (tid0 & ~63)), 16, 0,
+                                       2 /* non-temporal */);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
   float xt = (tid < tail) ? Vec<T>::load1(zr + nvec * N + tid) : kNegHuge;   // kNegHuge contributes 0
 
@@ -104,7 +126,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
   // The sampled token's own term is kept out of the running sum (see token_logprob_kernel).  Its element
   // is overwritten, in the packed registers, by the most negative finite value: one lane of one wavefront
   // takes this branch, the sweeps below stay free of control flow.
-  if (yk >= 0) {
+  if (yk >= 0 && yk < NV) {
 #pragma unroll
     for (int k = 0; k < NV; ++k)
       if (k == yk) q[k] = patch_lowest<T>(q[k], ysub);
@@ -120,6 +142,24 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
     accumulate<N>(x, scale, st);
     __builtin_amdgcn_sched_barrier(0);   // keeps the unpacked values of one vector short-lived
   }
+  if (NL > 0) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the copies into the slots have landed
+    if (yk >= NV) {                                        // the sampled token lies in a slot of this lane
+      u32x4* p = lrow + (yk - NV) * kRowThreads + tid;
+      *p = patch_lowest<T>(*p, ysub);
+    }
+    int tid1 = tid;
+    asm volatile("" : "+v"(tid1));
+#pragma unroll
+    for (int k = 0; k < NL; ++k) {
+      const int i = tid1 + (NV + k) * kRowThreads;
+      const u32x4 v = (i < nvec) ? lrow[k * kRowThreads + tid1] : lowest_fill<T>();
+      float x[N];
+      Vec<T>::unpack(v, x);
+      accumulate<N>(x, scale, st);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
   accumulate<1>(&xt, scale, st);
   st = wave_merge(st);
   if ((tid & 63) == 0) lds[tid >> 6] = st;
@@ -130,7 +170,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
     for (int w = 1; w < kRowWaves; ++w) t = merge(t, lds[w]);
     float lse, logp;
     if (y_ok) {
-      const double l1p = log1p_scaled((double)t.s, (double)t.m - (double)zy * (double)scale);
+      const double l1p = log1p_scaled(t.s, (double)t.m - (double)zy * (double)scale);
       logp = (float)(-l1p);
       lse = (float)((double)zy * (double)inv_temperature + l1p);
     } else {
@@ -154,15 +194,31 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
   for (int k = 0; k < NV; ++k) asm volatile("" : "+v"(q[k]) : "v"(shift));
 
   // ---- phase 2: softmax from the registers (the patched element comes out as 0) ----
+  // The vector indices are recomputed from an opaque copy of the thread index: otherwise the compiler keeps the
+  // byte offset of every vector alive from the loads to these stores, one more register per vector.
+  int tid2 = tid;
+  asm volatile("" : "+v"(tid2));
 #pragma unroll
   for (int k = 0; k < NV; ++k) {
-    const int i = tid + k * kRowThreads;
+    const int i = tid2 + k * kRowThreads;
     float x[N];
     Vec<T>::unpack(q[k], x);
 #pragma unroll
     for (int j = 0; j < N; ++j) x[j] = exp2_fast(__builtin_fmaf(x[j], scale, shift));
     if (i < nvec) store_stream(sv + i, Vec<T>::pack(x));
     __builtin_amdgcn_sched_barrier(0);
+  }
+  if (NL > 0) {
+#pragma unroll
+    for (int k = 0; k < NL; ++k) {
+      const int i = tid2 + (NV + k) * kRowThreads;
+      float x[N];
+      Vec<T>::unpack(lrow[k * kRowThreads + tid2], x);
+#pragma unroll
+      for (int j = 0; j < N; ++j) x[j] = exp2_fast(__builtin_fmaf(x[j], scale, shift));
+      if (i < nvec) store_stream(sv + i, Vec<T>::pack(x));
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
   if (tid < tail) Vec<T>::store1(sr + nvec * N + tid, exp2_fast(__builtin_fmaf(xt, scale, shift)));
   // the sampled token's element p_y - 1, by the lane that owns it, after its vector store has completed
@@ -172,11 +228,26 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
   }
 }
 
-template <typename T, int NV>
-void launch_nv(ais_ctx* ctx, const T* z, long long n_rows, int vocab, long long row_stride, const int* token_ids,
-               const unsigned char* valid, float inv_t, float* logp, float* lse, T* sgrad) {
-  fused_logprob_softmax_kernel<T, NV><<<dim3((unsigned)n_rows), dim3(kRowThreads), 0, ctx->stream>>>(
+constexpr int kSlotBytes = kRowThreads * 16;      // one LDS slot: a 16-byte vector per lane
+constexpr int kLdsSlots = 9;                      // 144 KiB of the 160 KiB of a compute unit
+
+template <typename T, int NV, int NL>
+int launch_nv(ais_ctx* ctx, const T* z, long long n_rows, int vocab, long long row_stride, const int* token_ids,
+              const unsigned char* valid, float inv_t, float* logp, float* lse, T* sgrad) {
+  auto kernel = fused_logprob_softmax_kernel<T, NV, NL>;
+  if (NL > 0) {
+    static bool attr_set_on[64] = {};             // the attribute belongs to the function on one device
+    bool& attr_set = attr_set_on[ctx->device & 63];
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, NL * kSlotBytes);
+      if (e != hipSuccess) return hip_fail(ctx, e);
+      attr_set = true;
+    }
+  }
+  kernel<<<dim3((unsigned)n_rows), dim3(kRowThreads), NL * kSlotBytes, ctx->stream>>>(
       z, row_stride, vocab, token_ids, valid, inv_t, logp, lse, sgrad, ctx->status_dev);
+  return AIS_OK;
 }
 
 // Vectors per lane needed for a row, or 0 when the row cannot be held (too wide, or not 16-byte aligned).
@@ -186,35 +257,37 @@ int vectors_per_lane(const void* z, const void* s, int vocab, long long row_stri
   const bool ok16 = reinterpret_cast<uintptr_t>(z) % 16 == 0 && reinterpret_cast<uintptr_t>(s) % 16 == 0 &&
                     (row_stride * (long long)sizeof(T)) % 16 == 0;
   const int need = (vocab / N + kRowThreads - 1) / kRowThreads;
-  return (ok16 && need <= 24) ? (need < 1 ? 1 : need) : 0;
+  return (ok16 && need <= 22 + kLdsSlots) ? (need < 1 ? 1 : need) : 0;
 }
 
 template <typename T>
-void launch_typed(ais_ctx* ctx, int need, const void* logits, long long n_rows, int vocab, long long row_stride,
-                  const int* token_ids, const unsigned char* valid, float inv_t, float* logp, float* lse,
-                  void* sgrad) {
+int launch_typed(ais_ctx* ctx, int need, const void* logits, long long n_rows, int vocab, long long row_stride,
+                 const int* token_ids, const unsigned char* valid, float inv_t, float* logp, float* lse,
+                 void* sgrad) {
   const T* z = static_cast<const T*>(logits);
   T* s = static_cast<T*>(sgrad);
   // NV is a compile-time constant (the row lives in named registers); sizes near the register limit get an
   // exact instantiation so that common vocabularies (e.g. 151,936 -> 19 vectors per lane) do not spill
-#define AIS_FUSED_CASE(NVAL)                                                                                 \
-  if (need <= NVAL) {                                                                                        \
-    launch_nv<T, NVAL>(ctx, z, n_rows, vocab, row_stride, token_ids, valid, inv_t, logp, lse, s);            \
-    return;                                                                                                  \
-  }
-  AIS_FUSED_CASE(4)
-  AIS_FUSED_CASE(8)
-  AIS_FUSED_CASE(12)
-  AIS_FUSED_CASE(16)
-  AIS_FUSED_CASE(17)
-  AIS_FUSED_CASE(18)
-  AIS_FUSED_CASE(19)
-  AIS_FUSED_CASE(20)
-  AIS_FUSED_CASE(21)
-  AIS_FUSED_CASE(22)
-  AIS_FUSED_CASE(23)
-  AIS_FUSED_CASE(24)
+#define AIS_FUSED_CASE(NEED, NVAL, NLVAL)                                                                    \
+  if (need <= NEED)                                                                                          \
+    return launch_nv<T, NVAL, NLVAL>(ctx, z, n_rows, vocab, row_stride, token_ids, valid, inv_t, logp, lse, s);
+  AIS_FUSED_CASE(4, 4, 0)
+  AIS_FUSED_CASE(8, 8, 0)
+  AIS_FUSED_CASE(12, 12, 0)
+  AIS_FUSED_CASE(16, 16, 0)
+  AIS_FUSED_CASE(17, 17, 0)
+  AIS_FUSED_CASE(18, 18, 0)
+  AIS_FUSED_CASE(19, 19, 0)
+  AIS_FUSED_CASE(20, 20, 0)
+  AIS_FUSED_CASE(21, 21, 0)
+  AIS_FUSED_CASE(22, 22, 0)
+  AIS_FUSED_CASE(23, 23, 0)
+  AIS_FUSED_CASE(24, 24, 0)
+  AIS_FUSED_CASE(27, 18, kLdsSlots)
+  AIS_FUSED_CASE(29, 20, kLdsSlots)
+  AIS_FUSED_CASE(31, 22, kLdsSlots)
 #undef AIS_FUSED_CASE
+  return AIS_ERR_SIZE;                            // not reached: vectors_per_lane() bounds `need`
 }
 
 }  // namespace
@@ -230,12 +303,12 @@ int launch_fused_logprob_softmax(ais_ctx* ctx, const void* logits, ais_dtype dty
   *used_registers = need > 0;
   if (need == 0 || n_rows == 0) return AIS_OK;
   ScopedTimer timer(ctx, AIS_K_FUSED);
-  if (dtype == AIS_BF16)
-    launch_typed<bf16_t>(ctx, need, logits, n_rows, vocab, row_stride, token_ids, valid, inv_temperature, logp_out,
-                         lse_out, sgrad);
-  else
-    launch_typed<float>(ctx, need, logits, n_rows, vocab, row_stride, token_ids, valid, inv_temperature, logp_out,
-                        lse_out, sgrad);
+  const int rc = dtype == AIS_BF16
+                     ? launch_typed<bf16_t>(ctx, need, logits, n_rows, vocab, row_stride, token_ids, valid,
+                                            inv_temperature, logp_out, lse_out, sgrad)
+                     : launch_typed<float>(ctx, need, logits, n_rows, vocab, row_stride, token_ids, valid,
+                                           inv_temperature, logp_out, lse_out, sgrad);
+  if (rc != AIS_OK) return rc;
   return hip_fail(ctx, hipGetLastError());
 }
 

@@ -98,7 +98,7 @@ __global__ __launch_bounds__(kSweepThreads) void token_logprob_kernel(
     if (y_ok) {
       // once per row, in fp64: r = S_o / e^{z_y/T};  logp = -log1p(r);  lse = z_y/T + log1p(r)
       const double ty = (double)zy * (double)scale;
-      const double l1p = log1p_scaled((double)t.s, (double)t.m - ty);
+      const double l1p = log1p_scaled(t.s, (double)t.m - ty);
       logp_out[row] = (float)(-l1p);
       lse_out[row] = (float)((double)zy * (double)inv_temperature + l1p);
     } else {

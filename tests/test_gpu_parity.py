@@ -68,6 +68,21 @@ def test_odd_vocabularies(ctx, vocab, dtype):
     P.check(ctx, batch)
 
 
+# every instantiation of the gradient sweep: 4 / 8 / 12 / 16 / 19 / 20 vectors per lane in one burst, two and three
+# bursts of 16, and the run-time loop over bursts beyond that (a lane's vector holds 8 bf16 or 4 fp32 elements)
+BURST_VOCABS = {"bf16": [40_001, 90_007, 120_011, 150_001, 160_003, 250_007, 300_017, 450_029],
+                "f32": [20_011, 45_007, 60_013, 75_011, 80_021, 125_003, 150_011, 230_003]}
+
+
+@pytest.mark.parametrize("dtype,vocab", [(d, v) for d in ("bf16", "f32") for v in BURST_VOCABS[d]])
+def test_every_row_width_class(ctx, dtype, vocab):
+    shape = W.RolloutShape("width", n_prompts=1, group_size=4, vocab=vocab, logits_dtype=dtype, sigma=3.0, boost=6.0,
+                           layout="padded", max_len=6, length_dist=("uniform", 2, 6), reward_p=0.5, seed=vocab)
+    batch = gen(shape)
+    batch.rewards[:] = torch.tensor([1, 0, 0, 1], dtype=torch.float32)
+    P.check(ctx, batch)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_padded_pitch_and_misaligned_base(ctx, dtype):
     """row_stride > vocab (a column slice of a wider matrix): vector body plus scalar tail; and a base pointer
