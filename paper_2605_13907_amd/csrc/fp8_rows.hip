@@ -1,7 +1,8 @@
 // Register-resident FP8-E4M3 quantisation: the row is read from HBM once and held in the register file of
 // one compute unit (1,024 threads x NV 16-byte vectors per lane) between the abs-max reduction that fixes
-// the scale and the pass that encodes with it.  Same results as the streaming two-pass kernel in fp8.hip,
-// which remains the route for rows that do not fit or are not 16-byte aligned.  (The fused rollout log-prob
+// the scale and the pass that encodes with it.  Rows of 25 to 31 vectors per lane keep their last 9 vectors
+// per lane in LDS, filled by direct global -> LDS copies.  Same results as the streaming two-pass kernel in
+// fp8.hip, which remains the route for rows that do not fit or are not 16-byte aligned.  (The fused rollout log-prob
 // stays a streaming kernel: its second pass is bound by arithmetic, and a workgroup that owns a whole compute
 // unit cannot overlap that arithmetic with another row's loads; measured slower than two streaming passes.)
 #include "ais_internal.h"
@@ -17,10 +18,17 @@ using namespace dev;
 
 constexpr int kRowThreads = 1024;
 constexpr int kRowWaves = kRowThreads / 64;
+constexpr int kSlotBytes = kRowThreads * 16;      // one LDS slot: a 16-byte vector per lane
+constexpr int kLdsSlots = 9;                      // 144 KiB of the 160 KiB of a compute unit
 
-// Loads the row, returns its scale (abs-max / 448) to every thread.  q[] and xt hold the row afterwards.
-template <typename T, int NV>
-__device__ __forceinline__ float load_row_and_scale(const T* zr, int vocab, u32x4 (&q)[NV], float& xt, float* lds) {
+typedef __attribute__((address_space(3))) void* lds_ptr;
+typedef const __attribute__((address_space(1))) void* glb_ptr;
+
+// Loads the row, returns its scale (abs-max / 448) to every thread.  q[] (vectors 0 .. NV - 1 of the lane), the
+// LDS slots lrow (vectors NV .. NV + NL - 1, 16 bytes at index 1024 (k - NV) + tid) and xt hold the row afterwards.
+template <typename T, int NV, int NL>
+__device__ __forceinline__ float load_row_and_scale(const T* zr, int vocab, u32x4 (&q)[NV], u32x4* lrow, float& xt,
+                                                    float* lds) {
   constexpr int N = Vec<T>::N;
   const int tid = threadIdx.x;
   const int nvec = vocab / N;
@@ -32,6 +40,19 @@ __device__ __forceinline__ float load_row_and_scale(const T* zr, int vocab, u32x
     const int i = tid + k * kRowThreads;
     q[k] = (i < nvec) ? load_stream(zv + i) : zero;
   }
+  if (NL > 0) {
+    // lane i of a wavefront deposits its 16 bytes at the wavefront's base + 16 i: the slot layout; lanes past the
+    // end of the row re-read its last vector (a valid address) and are masked where the slots are read
+    int tid0 = tid;
+    asm volatile("" : "+v"(tid0));
+#pragma unroll
+    for (int k = 0; k < NL; ++k) {
+      const int i = min(tid0 + (NV + k) * kRowThreads, nvec - 1);
+      __builtin_amdgcn_global_load_lds((glb_ptr)(zv + i), (lds_ptr)(lrow + k * kRowThreads + (tid0 & ~63)), 16, 0,
+                                       2 /* non-temporal */);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
   xt = (tid < tail) ? Vec<T>::load1(zr + nvec * N + tid) : 0.f;
   float amax = fabsf(xt);
 #pragma unroll
@@ -41,6 +62,21 @@ __device__ __forceinline__ float load_row_and_scale(const T* zr, int vocab, u32x
 #pragma unroll
     for (int j = 0; j < N; ++j) amax = fmaxf(amax, fabsf(x[j]));
     __builtin_amdgcn_sched_barrier(0);
+  }
+  if (NL > 0) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the copies into the slots have landed
+    int tid1 = tid;
+    asm volatile("" : "+v"(tid1));
+#pragma unroll
+    for (int k = 0; k < NL; ++k) {
+      const int i = tid1 + (NV + k) * kRowThreads;
+      const u32x4 v = (i < nvec) ? lrow[k * kRowThreads + tid1] : zero;
+      float x[N];
+      Vec<T>::unpack(v, x);
+#pragma unroll
+      for (int j = 0; j < N; ++j) amax = fmaxf(amax, fabsf(x[j]));
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
   amax = wave_max(amax);
   if ((tid & 63) == 0) lds[tid >> 6] = amax;
@@ -56,7 +92,7 @@ __device__ __forceinline__ float load_row_and_scale(const T* zr, int vocab, u32x
   return s;
 }
 
-template <typename T, int NV>
+template <typename T, int NV, int NL>
 __global__ __launch_bounds__(kRowThreads) void fp8_quantize_row_kernel(const T* __restrict__ logits,
                                                                        long long row_stride, int vocab,
                                                                        unsigned char* __restrict__ codes,
@@ -64,6 +100,8 @@ __global__ __launch_bounds__(kRowThreads) void fp8_quantize_row_kernel(const T* 
                                                                        float* __restrict__ scale_out) {
   constexpr int N = Vec<T>::N;
   __shared__ float lds[kRowWaves];
+  extern __shared__ __align__(16) unsigned char lds_slots[];
+  u32x4* lrow = reinterpret_cast<u32x4*>(lds_slots);
   const long long row = blockIdx.x;
   const int tid = threadIdx.x;
   const T* zr = logits + row * row_stride;
@@ -72,16 +110,17 @@ __global__ __launch_bounds__(kRowThreads) void fp8_quantize_row_kernel(const T* 
   const int tail = vocab - nvec * N;
   u32x4 q[NV];
   float xt;
-  const float s = load_row_and_scale<T, NV>(zr, vocab, q, xt, lds);
+  const float s = load_row_and_scale<T, NV, NL>(zr, vocab, q, lrow, xt, lds);
   if (tid == 0) scale_out[row] = s;
   const RowDivider d = make_divider(s);
+  // vector indices from an opaque copy of the thread index, so that no per-vector offset stays alive from the loads
+  int tid2 = tid;
+  asm volatile("" : "+v"(tid2));
   auto encode = [&](auto slow) {
     constexpr bool SLOW = decltype(slow)::value;
-#pragma unroll
-    for (int k = 0; k < NV; ++k) {
-      const int i = tid + k * kRowThreads;
+    auto encode_vector = [&](u32x4 v, int i) {
       float x[N];
-      Vec<T>::unpack(q[k], x);
+      Vec<T>::unpack(v, x);
       uint32_t w[N / 4];
 #pragma unroll
       for (int j = 0; j < N / 4; ++j)
@@ -95,7 +134,18 @@ __global__ __launch_bounds__(kRowThreads) void fp8_quantize_row_kernel(const T* 
           *reinterpret_cast<uint32_t*>(cr + (long long)i * N) = w[0];
         }
       }
+    };
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      encode_vector(q[k], tid2 + k * kRowThreads);
       __builtin_amdgcn_sched_barrier(0);
+    }
+    if (NL > 0) {
+#pragma unroll
+      for (int k = 0; k < NL; ++k) {
+        encode_vector(lrow[k * kRowThreads + tid2], tid2 + (NV + k) * kRowThreads);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
     if (tid < tail) cr[nvec * N + tid] = (unsigned char)(to_e4m3x2(divide<SLOW>(xt, d), 0.f) & 0xffu);
   };
@@ -107,16 +157,46 @@ int vectors_per_lane(const void* z, int vocab, long long row_stride) {
   constexpr int N = Vec<T>::N;
   const bool ok16 = reinterpret_cast<uintptr_t>(z) % 16 == 0 && (row_stride * (long long)sizeof(T)) % 16 == 0;
   const int need = (vocab / N + kRowThreads - 1) / kRowThreads;
-  return (ok16 && need <= 24) ? (need < 1 ? 1 : need) : 0;
+  return (ok16 && need <= 22 + kLdsSlots) ? (need < 1 ? 1 : need) : 0;
 }
 
-#define AIS_ROW_DISPATCH(NEED, CALL)          \
-  if (NEED <= 4) { CALL(4) }                  \
-  else if (NEED <= 8) { CALL(8) }             \
-  else if (NEED <= 12) { CALL(12) }           \
-  else if (NEED <= 16) { CALL(16) }           \
-  else if (NEED <= 20) { CALL(20) }           \
-  else { CALL(24) }
+template <typename T, int NV, int NL>
+bool launch_rows(ais_ctx* ctx, const T* z, long long n_rows, int vocab, long long row_stride, unsigned char* codes,
+                 long long codes_stride, float* scale_out) {
+  auto kernel = fp8_quantize_row_kernel<T, NV, NL>;
+  if (NL > 0) {
+    static bool attr_set_on[64] = {};             // the attribute belongs to the function on one device
+    bool& attr_set = attr_set_on[ctx->device & 63];
+    if (!attr_set) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              NL * kSlotBytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;                              // the caller falls back to the streaming kernel
+      }
+      attr_set = true;
+    }
+  }
+  kernel<<<dim3((unsigned)n_rows), dim3(kRowThreads), NL * kSlotBytes, ctx->stream>>>(z, row_stride, vocab, codes,
+                                                                                       codes_stride, scale_out);
+  return true;
+}
+
+template <typename T>
+bool dispatch_rows(ais_ctx* ctx, int need, const T* z, long long n_rows, int vocab, long long row_stride,
+                   unsigned char* codes, long long codes_stride, float* scale_out) {
+#define AIS_ROW_CASE(NEED, NVAL, NLVAL) \
+  if (need <= NEED) return launch_rows<T, NVAL, NLVAL>(ctx, z, n_rows, vocab, row_stride, codes, codes_stride, scale_out);
+  AIS_ROW_CASE(4, 4, 0)
+  AIS_ROW_CASE(8, 8, 0)
+  AIS_ROW_CASE(12, 12, 0)
+  AIS_ROW_CASE(16, 16, 0)
+  AIS_ROW_CASE(20, 20, 0)
+  AIS_ROW_CASE(24, 24, 0)
+  AIS_ROW_CASE(27, 18, kLdsSlots)
+  AIS_ROW_CASE(31, 22, kLdsSlots)
+#undef AIS_ROW_CASE
+  return false;
+}
 
 }  // namespace
 
@@ -125,23 +205,16 @@ bool try_fp8_quantize_rows(ais_ctx* ctx, const void* logits, ais_dtype dtype, lo
                            long long row_stride, unsigned char* codes, long long codes_stride, float* scale_out) {
   const int store_align = dtype == AIS_BF16 ? 8 : 4;
   if (reinterpret_cast<uintptr_t>(codes) % store_align != 0 || codes_stride % store_align != 0) return false;
-  dim3 grid((unsigned)n_rows), block(kRowThreads);
   if (dtype == AIS_BF16) {
     const int need = vectors_per_lane<bf16_t>(logits, vocab, row_stride);
     if (need == 0) return false;
-    const bf16_t* z = static_cast<const bf16_t*>(logits);
-#define CALL(NVAL) fp8_quantize_row_kernel<bf16_t, NVAL><<<grid, block, 0, ctx->stream>>>(z, row_stride, vocab, codes, codes_stride, scale_out);
-    AIS_ROW_DISPATCH(need, CALL)
-#undef CALL
-  } else {
-    const int need = vectors_per_lane<float>(logits, vocab, row_stride);
-    if (need == 0) return false;
-    const float* z = static_cast<const float*>(logits);
-#define CALL(NVAL) fp8_quantize_row_kernel<float, NVAL><<<grid, block, 0, ctx->stream>>>(z, row_stride, vocab, codes, codes_stride, scale_out);
-    AIS_ROW_DISPATCH(need, CALL)
-#undef CALL
+    return dispatch_rows<bf16_t>(ctx, need, static_cast<const bf16_t*>(logits), n_rows, vocab, row_stride, codes,
+                                 codes_stride, scale_out);
   }
-  return true;
+  const int need = vectors_per_lane<float>(logits, vocab, row_stride);
+  if (need == 0) return false;
+  return dispatch_rows<float>(ctx, need, static_cast<const float*>(logits), n_rows, vocab, row_stride, codes,
+                              codes_stride, scale_out);
 }
 
 }  // namespace ais

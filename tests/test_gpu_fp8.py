@@ -72,6 +72,24 @@ def test_random_rows(ctx, dtype, vocab):
     assert np.abs(lp.double().cpu().numpy() - ref).max() <= LOGP_ATOL
 
 
+# every instantiation of the register-resident quantise kernel: 4 / 8 / 12 / 16 / 20 / 24 vectors per lane, 18 + 9 and
+# 22 + 9 with the last nine in LDS, and the streaming route beyond (a vector holds 8 bf16 or 4 fp32 elements)
+ROW_VOCABS = {"bf16": [40_001, 90_007, 120_011, 151_936, 190_003, 210_007, 248_320, 260_011],
+              "f32": [20_011, 45_007, 60_013, 75_011, 95_003, 105_001, 124_003, 130_007]}
+
+
+@pytest.mark.parametrize("dtype,vocab", [(d, v) for d in ("bf16", "f32") for v in ROW_VOCABS[d]])
+def test_every_row_width_class(ctx, dtype, vocab):
+    dt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    g = torch.Generator(device="cuda")
+    g.manual_seed(vocab)
+    z = (torch.randn(5, vocab, generator=g, device="cuda") * 3.0).to(dt)
+    z[0] = 0
+    z[1, vocab - 1] = -41.0          # the abs-max in the ragged tail
+    z[2, vocab // 2] = 97.0
+    check_quant(ctx, z)
+
+
 def all_ones_scale_absmax():
     """An fp32 abs-max whose scale RN(amax / 448) has an all-ones significand (the divisor the reciprocal
     scheme must hand to the true division), found by search on the CPU."""
