@@ -113,7 +113,8 @@ typedef struct ais_diag {
 /* ---- context ------------------------------------------------------------------------------ */
 
 /* Creates a context on GPU `device` that launches on `hip_stream` (a hipStream_t; NULL = the
- * default stream).  *out is host memory.  Allocates a small device workspace. */
+ * default stream).  *out is host memory.  Allocates a small device workspace.  Device indices
+ * of 64 and above are rejected with AIS_ERR_SIZE. */
 int ais_create(ais_ctx** out, int device, void* hip_stream);
 /* Waits for the context's stream, frees the workspace.  NULL is allowed. */
 int ais_destroy(ais_ctx* ctx);

@@ -13,6 +13,7 @@ namespace ais {
 constexpr int kSweepThreads = 256;     // one workgroup (4 wavefronts) streams one logits row
 constexpr int kTileThreads = 256;      // workgroup of the per-row scalar kernels
 constexpr int kTileRows = 1024;        // rows of one response handled by one such workgroup
+constexpr int kMaxDevices = 64;        // device indices a context may be created on
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 

@@ -151,6 +151,7 @@ int ais_create(ais_ctx** out, int device, void* hip_stream) {
     (void)hipGetLastError();
     return AIS_ERR_HIP;
   }
+  if (device >= kMaxDevices) return AIS_ERR_SIZE;   // per-device launch attributes are cached in fixed tables
   ais_ctx* ctx = new (std::nothrow) ais_ctx;
   if (ctx == nullptr) return AIS_ERR_NOMEM;
   ctx->device = device;

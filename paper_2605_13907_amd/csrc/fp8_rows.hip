@@ -165,8 +165,8 @@ bool launch_rows(ais_ctx* ctx, const T* z, long long n_rows, int vocab, long lon
                  long long codes_stride, float* scale_out) {
   auto kernel = fp8_quantize_row_kernel<T, NV, NL>;
   if (NL > 0) {
-    static bool attr_set_on[64] = {};             // the attribute belongs to the function on one device
-    bool& attr_set = attr_set_on[ctx->device & 63];
+    static bool attr_set_on[kMaxDevices] = {};             // the attribute belongs to the function on one device
+    bool& attr_set = attr_set_on[ctx->device];
     if (!attr_set) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                               NL * kSlotBytes) != hipSuccess) {

@@ -236,8 +236,8 @@ int launch_nv(ais_ctx* ctx, const T* z, long long n_rows, int vocab, long long r
               const unsigned char* valid, float inv_t, float* logp, float* lse, T* sgrad) {
   auto kernel = fused_logprob_softmax_kernel<T, NV, NL>;
   if (NL > 0) {
-    static bool attr_set_on[64] = {};             // the attribute belongs to the function on one device
-    bool& attr_set = attr_set_on[ctx->device & 63];
+    static bool attr_set_on[kMaxDevices] = {};             // the attribute belongs to the function on one device
+    bool& attr_set = attr_set_on[ctx->device];
     if (!attr_set) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, NL * kSlotBytes);

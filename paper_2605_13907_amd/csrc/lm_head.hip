@@ -685,8 +685,8 @@ int launch_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long ld_h, con
                            float* part_m, float* part_s, float* zy, int* row_index, int* row_pos, void* dev_plan,
                            float* logp_out, float* lse_out) {
   constexpr int kStreamLds = AIS_LM_STAGES * kStStageBytes;
-  static bool attr_set_on[64] = {};                 // the attribute belongs to the function on one device
-  bool& attr_set = attr_set_on[ctx->device & 63];
+  static bool attr_set_on[kMaxDevices] = {};                 // the attribute belongs to the function on one device
+  bool& attr_set = attr_set_on[ctx->device];
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_stream_kernel<AIS_LM_STAGES>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kStreamLds);

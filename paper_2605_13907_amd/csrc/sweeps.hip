@@ -190,7 +190,8 @@ __global__ __launch_bounds__(kBurstThreads) void dlogits_burst_kernel(
   const float dzy = c * expm1f(logp[row]);
 
   const int n_base = NSEG > 0 ? NSEG * NV * kBurstThreads : nvec;
-#pragma unroll
+  constexpr int kUnrollSegments = NSEG > 0 ? NSEG : 1;
+#pragma unroll kUnrollSegments
   for (int base = 0; base < n_base; base += NV * kBurstThreads) {
     u32x4 q[NV];
 #pragma unroll
