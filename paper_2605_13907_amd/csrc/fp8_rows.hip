@@ -1,6 +1,6 @@
 // Register-resident FP8-E4M3 quantisation: the row is read from HBM once and held in the register file of
 // one compute unit (1,024 threads x NV 16-byte vectors per lane) between the abs-max reduction that fixes
-// the scale and the pass that encodes with it.  Rows of 25 to 31 vectors per lane keep their last 9 vectors
+// the scale and the pass that encodes with it.  Rows of 25 to 33 vectors per lane keep their last 9 vectors
 // per lane in LDS, filled by direct global -> LDS copies.  Same results as the streaming two-pass kernel in
 // fp8.hip, which remains the route for rows that do not fit or are not 16-byte aligned.  (The fused rollout log-prob
 // stays a streaming kernel: its second pass is bound by arithmetic, and a workgroup that owns a whole compute
@@ -26,7 +26,9 @@ typedef const __attribute__((address_space(1))) void* glb_ptr;
 
 // Loads the row, returns its scale (abs-max / 448) to every thread.  q[] (vectors 0 .. NV - 1 of the lane), the
 // LDS slots lrow (vectors NV .. NV + NL - 1, 16 bytes at index 1024 (k - NV) + tid) and xt hold the row afterwards.
-template <typename T, int NV, int NL>
+// KFULL: the caller promises that the row has more than KFULL * 1024 vectors, so vectors 0 .. KFULL - 1 of every
+// lane exist and are loaded without a bounds branch.
+template <typename T, int NV, int NL, int KFULL>
 __device__ __forceinline__ float load_row_and_scale(const T* zr, int vocab, u32x4 (&q)[NV], u32x4* lrow, float& xt,
                                                     float* lds) {
   constexpr int N = Vec<T>::N;
@@ -38,7 +40,8 @@ __device__ __forceinline__ float load_row_and_scale(const T* zr, int vocab, u32x
 #pragma unroll
   for (int k = 0; k < NV; ++k) {
     const int i = tid + k * kRowThreads;
-    q[k] = (i < nvec) ? load_stream(zv + i) : zero;
+    if (k < KFULL) q[k] = load_stream(zv + i);
+    else q[k] = (i < nvec) ? load_stream(zv + i) : zero;
   }
   if (NL > 0) {
     // lane i of a wavefront deposits its 16 bytes at the wavefront's base + 16 i: the slot layout; lanes past the
@@ -69,10 +72,10 @@ __device__ __forceinline__ float load_row_and_scale(const T* zr, int vocab, u32x
     asm volatile("" : "+v"(tid1));
 #pragma unroll
     for (int k = 0; k < NL; ++k) {
-      const int i = tid1 + (NV + k) * kRowThreads;
-      const u32x4 v = (i < nvec) ? lrow[k * kRowThreads + tid1] : zero;
+      // every slot holds data (lanes past the end of the row hold a copy of its last vector, which changes no
+      // maximum); read without a branch, so that the reads stay in this order
       float x[N];
-      Vec<T>::unpack(v, x);
+      Vec<T>::unpack(lrow[k * kRowThreads + tid1], x);
 #pragma unroll
       for (int j = 0; j < N; ++j) amax = fmaxf(amax, fabsf(x[j]));
       __builtin_amdgcn_sched_barrier(0);
@@ -92,7 +95,7 @@ __device__ __forceinline__ float load_row_and_scale(const T* zr, int vocab, u32x
   return s;
 }
 
-template <typename T, int NV, int NL>
+template <typename T, int NV, int NL, int KFULL>
 __global__ __launch_bounds__(kRowThreads) void fp8_quantize_row_kernel(const T* __restrict__ logits,
                                                                        long long row_stride, int vocab,
                                                                        unsigned char* __restrict__ codes,
@@ -110,7 +113,7 @@ __global__ __launch_bounds__(kRowThreads) void fp8_quantize_row_kernel(const T* 
   const int tail = vocab - nvec * N;
   u32x4 q[NV];
   float xt;
-  const float s = load_row_and_scale<T, NV, NL>(zr, vocab, q, lrow, xt, lds);
+  const float s = load_row_and_scale<T, NV, NL, KFULL>(zr, vocab, q, lrow, xt, lds);
   if (tid == 0) scale_out[row] = s;
   const RowDivider d = make_divider(s);
   // vector indices from an opaque copy of the thread index, so that no per-vector offset stays alive from the loads
@@ -157,13 +160,13 @@ int vectors_per_lane(const void* z, int vocab, long long row_stride) {
   constexpr int N = Vec<T>::N;
   const bool ok16 = reinterpret_cast<uintptr_t>(z) % 16 == 0 && (row_stride * (long long)sizeof(T)) % 16 == 0;
   const int need = (vocab / N + kRowThreads - 1) / kRowThreads;
-  return (ok16 && need <= 22 + kLdsSlots) ? (need < 1 ? 1 : need) : 0;
+  return (ok16 && need <= 24 + kLdsSlots) ? (need < 1 ? 1 : need) : 0;
 }
 
-template <typename T, int NV, int NL>
+template <typename T, int NV, int NL, int KFULL>
 bool launch_rows(ais_ctx* ctx, const T* z, long long n_rows, int vocab, long long row_stride, unsigned char* codes,
                  long long codes_stride, float* scale_out) {
-  auto kernel = fp8_quantize_row_kernel<T, NV, NL>;
+  auto kernel = fp8_quantize_row_kernel<T, NV, NL, KFULL>;
   if (NL > 0) {
     static bool attr_set_on[kMaxDevices] = {};             // the attribute belongs to the function on one device
     bool& attr_set = attr_set_on[ctx->device];
@@ -184,16 +187,19 @@ bool launch_rows(ais_ctx* ctx, const T* z, long long n_rows, int vocab, long lon
 template <typename T>
 bool dispatch_rows(ais_ctx* ctx, int need, const T* z, long long n_rows, int vocab, long long row_stride,
                    unsigned char* codes, long long codes_stride, float* scale_out) {
-#define AIS_ROW_CASE(NEED, NVAL, NLVAL) \
-  if (need <= NEED) return launch_rows<T, NVAL, NLVAL>(ctx, z, n_rows, vocab, row_stride, codes, codes_stride, scale_out);
-  AIS_ROW_CASE(4, 4, 0)
-  AIS_ROW_CASE(8, 8, 0)
-  AIS_ROW_CASE(12, 12, 0)
-  AIS_ROW_CASE(16, 16, 0)
-  AIS_ROW_CASE(20, 20, 0)
-  AIS_ROW_CASE(24, 24, 0)
-  AIS_ROW_CASE(27, 18, kLdsSlots)
-  AIS_ROW_CASE(31, 22, kLdsSlots)
+// PREV: the widest row of the previous class; a row that reaches this one has more than PREV * 1024 vectors
+#define AIS_ROW_CASE(PREV, NEED, NVAL, NLVAL) \
+  if (need <= NEED)                           \
+    return launch_rows<T, NVAL, NLVAL, PREV>(ctx, z, n_rows, vocab, row_stride, codes, codes_stride, scale_out);
+  AIS_ROW_CASE(0, 4, 4, 0)
+  AIS_ROW_CASE(4, 8, 8, 0)
+  AIS_ROW_CASE(8, 12, 12, 0)
+  AIS_ROW_CASE(12, 16, 16, 0)
+  AIS_ROW_CASE(16, 20, 20, 0)
+  AIS_ROW_CASE(20, 24, 24, 0)
+  AIS_ROW_CASE(24, 27, 18, kLdsSlots)
+  AIS_ROW_CASE(27, 31, 22, kLdsSlots)
+  AIS_ROW_CASE(31, 33, 24, kLdsSlots)
 #undef AIS_ROW_CASE
   return false;
 }

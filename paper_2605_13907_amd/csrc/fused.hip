@@ -13,7 +13,7 @@
 // NV 16-byte vectors per lane.  All NV loads of a lane are issued back to back, so the whole row is in
 // flight at once and memory latency is paid once per row.  Rows wider than 24 vectors per lane keep their
 // last 9 vectors per lane in LDS (144 KiB of the compute unit's 160), which are filled by direct
-// global -> LDS copies and never pass through registers on the way in: up to 31 vectors per lane, 253,952
+// global -> LDS copies and never pass through registers on the way in: up to 33 vectors per lane, 270,336
 // bf16 elements.  Rows wider than that fall back to the two-pass kernels.
 #include "ais_internal.h"
 #include "device_utils.h"
@@ -54,10 +54,12 @@ template <> __device__ __forceinline__ u32x4 patch_lowest<float>(u32x4 q, int su
 typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef const __attribute__((address_space(1))) void* glb_ptr;
 
-// grid.x = n_rows, block = kRowThreads.  Requires 16-byte aligned rows and vocab / N <= (NV + NL) * kRowThreads.
+// grid.x = n_rows, block = kRowThreads.  Requires 16-byte aligned rows and
+// KFULL * kRowThreads < vocab / N <= (NV + NL) * kRowThreads: vectors 0 .. KFULL - 1 of every lane exist and are
+// loaded and stored without a bounds branch.
 // Vector k of a lane (elements N * (tid + 1024 k) ..) lives in register q[k] for k < NV and in LDS slot k - NV
 // (16 bytes at byte offset 16 * (1024 (k - NV) + tid) of the dynamic LDS) for NV <= k < NV + NL.
-template <typename T, int NV, int NL>
+template <typename T, int NV, int NL, int KFULL>
 __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
     const T* logits, long long row_stride, int vocab, const int* __restrict__ token_ids,
     const unsigned char* __restrict__ valid, float inv_temperature, float* __restrict__ logp_out,
@@ -96,7 +98,8 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
 #pragma unroll
   for (int k = 0; k < NV; ++k) {
     const int i = tid + k * kRowThreads;
-    q[k] = (i < nvec) ? load_stream(zv + i) : lowest_fill<T>();
+    if (k < KFULL) q[k] = load_stream(zv + i);       // the launcher promises nvec > KFULL * kRowThreads
+    else q[k] = (i < nvec) ? load_stream(zv + i) : lowest_fill<T>();
   }
   // the LDS slots: lane i of a wavefront deposits its 16 bytes at the wavefront's base + 16 i, which is the
   // slot layout; lanes past the end of the row re-read its last vector (a valid address) and are masked later
@@ -153,9 +156,15 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
 #pragma unroll
     for (int k = 0; k < NL; ++k) {
       const int i = tid1 + (NV + k) * kRowThreads;
-      const u32x4 v = (i < nvec) ? lrow[k * kRowThreads + tid1] : lowest_fill<T>();
+      // every slot holds data (lanes past the end of the row hold a copy of its last vector); read without a
+      // branch, so that the reads stay in this order, and mask afterwards where the row can end
+      const u32x4 v = lrow[k * kRowThreads + tid1];
       float x[N];
       Vec<T>::unpack(v, x);
+      if (NV + k >= KFULL) {
+#pragma unroll
+        for (int j = 0; j < N; ++j) x[j] = (i < nvec) ? x[j] : kNegHuge;
+      }
       accumulate<N>(x, scale, st);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -205,7 +214,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
     Vec<T>::unpack(q[k], x);
 #pragma unroll
     for (int j = 0; j < N; ++j) x[j] = exp2_fast(__builtin_fmaf(x[j], scale, shift));
-    if (i < nvec) store_stream(sv + i, Vec<T>::pack(x));
+    if (k < KFULL || i < nvec) store_stream(sv + i, Vec<T>::pack(x));
     __builtin_amdgcn_sched_barrier(0);
   }
   if (NL > 0) {
@@ -231,10 +240,10 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
 constexpr int kSlotBytes = kRowThreads * 16;      // one LDS slot: a 16-byte vector per lane
 constexpr int kLdsSlots = 9;                      // 144 KiB of the 160 KiB of a compute unit
 
-template <typename T, int NV, int NL>
+template <typename T, int NV, int NL, int KFULL>
 int launch_nv(ais_ctx* ctx, const T* z, long long n_rows, int vocab, long long row_stride, const int* token_ids,
               const unsigned char* valid, float inv_t, float* logp, float* lse, T* sgrad) {
-  auto kernel = fused_logprob_softmax_kernel<T, NV, NL>;
+  auto kernel = fused_logprob_softmax_kernel<T, NV, NL, KFULL>;
   if (NL > 0) {
     static bool attr_set_on[kMaxDevices] = {};             // the attribute belongs to the function on one device
     bool& attr_set = attr_set_on[ctx->device];
@@ -257,7 +266,7 @@ int vectors_per_lane(const void* z, const void* s, int vocab, long long row_stri
   const bool ok16 = reinterpret_cast<uintptr_t>(z) % 16 == 0 && reinterpret_cast<uintptr_t>(s) % 16 == 0 &&
                     (row_stride * (long long)sizeof(T)) % 16 == 0;
   const int need = (vocab / N + kRowThreads - 1) / kRowThreads;
-  return (ok16 && need <= 22 + kLdsSlots) ? (need < 1 ? 1 : need) : 0;
+  return (ok16 && need <= 24 + kLdsSlots) ? (need < 1 ? 1 : need) : 0;
 }
 
 template <typename T>
@@ -268,24 +277,27 @@ int launch_typed(ais_ctx* ctx, int need, const void* logits, long long n_rows, i
   T* s = static_cast<T*>(sgrad);
   // NV is a compile-time constant (the row lives in named registers); sizes near the register limit get an
   // exact instantiation so that common vocabularies (e.g. 151,936 -> 19 vectors per lane) do not spill
-#define AIS_FUSED_CASE(NEED, NVAL, NLVAL)                                                                    \
-  if (need <= NEED)                                                                                          \
-    return launch_nv<T, NVAL, NLVAL>(ctx, z, n_rows, vocab, row_stride, token_ids, valid, inv_t, logp, lse, s);
-  AIS_FUSED_CASE(4, 4, 0)
-  AIS_FUSED_CASE(8, 8, 0)
-  AIS_FUSED_CASE(12, 12, 0)
-  AIS_FUSED_CASE(16, 16, 0)
-  AIS_FUSED_CASE(17, 17, 0)
-  AIS_FUSED_CASE(18, 18, 0)
-  AIS_FUSED_CASE(19, 19, 0)
-  AIS_FUSED_CASE(20, 20, 0)
-  AIS_FUSED_CASE(21, 21, 0)
-  AIS_FUSED_CASE(22, 22, 0)
-  AIS_FUSED_CASE(23, 23, 0)
-  AIS_FUSED_CASE(24, 24, 0)
-  AIS_FUSED_CASE(27, 18, kLdsSlots)
-  AIS_FUSED_CASE(29, 20, kLdsSlots)
-  AIS_FUSED_CASE(31, 22, kLdsSlots)
+  // PREV: the widest row of the previous class; a row that reaches this one has more than PREV * 1024 vectors
+#define AIS_FUSED_CASE(PREV, NEED, NVAL, NLVAL)                                                         \
+  if (need <= NEED)                                                                                     \
+    return launch_nv<T, NVAL, NLVAL, PREV>(ctx, z, n_rows, vocab, row_stride, token_ids, valid, inv_t, \
+                                           logp, lse, s);
+  AIS_FUSED_CASE(0, 4, 4, 0)
+  AIS_FUSED_CASE(4, 8, 8, 0)
+  AIS_FUSED_CASE(8, 12, 12, 0)
+  AIS_FUSED_CASE(12, 16, 16, 0)
+  AIS_FUSED_CASE(16, 17, 17, 0)
+  AIS_FUSED_CASE(17, 18, 18, 0)
+  AIS_FUSED_CASE(18, 19, 19, 0)
+  AIS_FUSED_CASE(19, 20, 20, 0)
+  AIS_FUSED_CASE(20, 21, 21, 0)
+  AIS_FUSED_CASE(21, 22, 22, 0)
+  AIS_FUSED_CASE(22, 23, 23, 0)
+  AIS_FUSED_CASE(23, 24, 24, 0)
+  AIS_FUSED_CASE(24, 27, 18, kLdsSlots)
+  AIS_FUSED_CASE(27, 29, 20, kLdsSlots)
+  AIS_FUSED_CASE(29, 31, 22, kLdsSlots)
+  AIS_FUSED_CASE(31, 33, 24, kLdsSlots)
 #undef AIS_FUSED_CASE
   return AIS_ERR_SIZE;                            // not reached: vectors_per_lane() bounds `need`
 }

@@ -74,8 +74,8 @@ def test_random_rows(ctx, dtype, vocab):
 
 # every instantiation of the register-resident quantise kernel: 4 / 8 / 12 / 16 / 20 / 24 vectors per lane, 18 + 9 and
 # 22 + 9 with the last nine in LDS, and the streaming route beyond (a vector holds 8 bf16 or 4 fp32 elements)
-ROW_VOCABS = {"bf16": [40_001, 90_007, 120_011, 151_936, 190_003, 210_007, 248_320, 260_011],
-              "f32": [20_011, 45_007, 60_013, 75_011, 95_003, 105_001, 124_003, 130_007]}
+ROW_VOCABS = {"bf16": [40_001, 90_007, 120_011, 151_936, 190_003, 210_007, 248_320, 260_011, 270_336, 275_003],
+              "f32": [20_011, 45_007, 60_013, 75_011, 95_003, 105_001, 124_003, 130_007, 135_168, 137_501]}
 
 
 @pytest.mark.parametrize("dtype,vocab", [(d, v) for d in ("bf16", "f32") for v in ROW_VOCABS[d]])

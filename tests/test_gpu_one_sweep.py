@@ -66,14 +66,26 @@ def test_tiny_fp32(ctx):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("vocab", [1, 5, 1003, 8200, 40_001, 98_312, 110_597, 127_000, 140_000])
+@pytest.mark.parametrize("vocab", [1, 5, 1003, 8200, 40_001, 98_312, 110_597, 122_881, 127_000, 132_501, 140_000])
 def test_odd_vocabularies(ctx, vocab, dtype):
     shape = W.RolloutShape("odd", n_prompts=2, group_size=4, vocab=vocab, logits_dtype=dtype, sigma=2.5, boost=4.0,
                            layout="padded", max_len=6, length_dist=("uniform", 1, 6), reward_p=0.5, seed=vocab)
-    # fp32: 98,312 needs 25 slots per lane (18 + 9 in LDS), 110,597 needs 28 (20 + 9), 127,000 needs 31
-    # (22 + 9), 140,000 needs 35 and takes the two-pass route; bf16 rows of these widths stay in registers
+    # fp32: 98,312 needs 25 slots per lane (18 + 9 in LDS), 110,597 needs 28 (20 + 9), 122,881 needs 31 (22 + 9, only
+    # one vector of the last slot exists), 127,000 needs 32 and 132,501 needs 33 (24 + 9), 140,000 needs 35 and
+    # takes the two-pass route; bf16 rows of these widths stay in registers
     batch = W.generate(shape, "cuda")
     batch.rewards[:] = torch.tensor([1, 0, 0, 1, 0, 0, 1, 0], dtype=torch.float32)
+    check_one_sweep(ctx, batch)
+
+
+@pytest.mark.parametrize("vocab", [200_003, 230_011, 248_327, 262_147, 268_001, 270_336, 270_337, 280_001])
+def test_wide_bf16_rows(ctx, vocab):
+    """bf16 rows of 25 to 33 vectors per lane (the last 9 in LDS), the widest row that fits (270,336), and the first
+    widths that do not and take the two-pass route."""
+    shape = W.RolloutShape("wide", n_prompts=1, group_size=4, vocab=vocab, logits_dtype="bf16", sigma=2.5, boost=4.0,
+                           layout="padded", max_len=5, length_dist=("uniform", 2, 5), reward_p=0.5, seed=vocab)
+    batch = W.generate(shape, "cuda")
+    batch.rewards[:] = torch.tensor([1, 0, 0, 1], dtype=torch.float32)
     check_one_sweep(ctx, batch)
 
 
