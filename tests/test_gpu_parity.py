@@ -68,10 +68,14 @@ def test_odd_vocabularies(ctx, vocab, dtype):
     P.check(ctx, batch)
 
 
-# every instantiation of the gradient sweep: 4 / 8 / 12 / 16 / 19 / 20 vectors per lane in one burst, two and three
-# bursts of 16, and the run-time loop over bursts beyond that (a lane's vector holds 8 bf16 or 4 fp32 elements)
-BURST_VOCABS = {"bf16": [40_001, 90_007, 120_011, 150_001, 160_003, 250_007, 300_017, 450_029],
-                "f32": [20_011, 45_007, 60_013, 75_011, 80_021, 125_003, 150_011, 230_003]}
+# every instantiation of the gradient sweep: 4 / 8 / 12 and each of 13 .. 20 vectors per lane in one burst, two and
+# three bursts of 16, and the run-time loop over bursts beyond that (a lane's vector holds 8 bf16 or 4 fp32
+# elements); around 19 x 1,024 vectors also a row that fills its last vector slot exactly, one element more (a
+# scalar tail), and one vector more (the next class, with a single lane in its last slot)
+BURST_VOCABS = {"bf16": [40_001, 90_007, 100_003, 110_001, 120_011, 126_464, 135_007, 143_003, 150_001, 155_648, 155_649,
+                         155_656, 160_003, 250_007, 300_017, 450_029],
+                "f32": [20_011, 45_007, 50_001, 55_001, 60_013, 63_233, 67_501, 71_503, 75_011, 77_824, 77_825, 77_828,
+                        80_021, 125_003, 150_011, 230_003]}
 
 
 @pytest.mark.parametrize("dtype,vocab", [(d, v) for d in ("bf16", "f32") for v in BURST_VOCABS[d]])
