@@ -106,6 +106,8 @@ bool try_fp8_quantize_rows(ais_ctx* ctx, const void* logits, ais_dtype dtype, lo
                            long long row_stride, unsigned char* codes, long long codes_stride, float* scale_out);
 int launch_fp8_dequantize(ais_ctx* ctx, const unsigned char* codes, long long codes_stride, const float* scale,
                           long long n_rows, int vocab, void* out, ais_dtype dtype, long long out_stride);
+bool try_fp8_dequantize_burst(ais_ctx* ctx, const unsigned char* codes, long long codes_stride, const float* scale,
+                              long long n_rows, int vocab, void* out, ais_dtype dtype, long long out_stride);
 int launch_fp8_rollout_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,
                                long long row_stride, const int* token_ids, const unsigned char* valid,
                                float* logp_out);

@@ -218,6 +218,8 @@ int launch_fp8_dequantize(ais_ctx* ctx, const unsigned char* codes, long long co
   if (n_rows == 0) return AIS_OK;
   dim3 grid((unsigned)n_rows), block(kSweepThreads);
   ScopedTimer timer(ctx, AIS_K_FP8_DEQUANT);
+  if (try_fp8_dequantize_burst(ctx, codes, codes_stride, scale, n_rows, vocab, out, dtype, out_stride))
+    return hip_fail(ctx, hipGetLastError());
   if (dtype == AIS_BF16) {
     bf16_t* o = static_cast<bf16_t*>(out);
     if (aligned(o, out_stride * 2, 16) && aligned(codes, codes_stride, 8))

@@ -1,3 +1,6 @@
+// The FP8-E4M3 kernels that give one workgroup of 1,024 threads a whole row: the register-resident quantisation
+// and the burst form of the dequantisation (further down).
+//
 // Register-resident FP8-E4M3 quantisation: the row is read from HBM once and held in the register file of
 // one compute unit (1,024 threads x NV 16-byte vectors per lane) between the abs-max reduction that fixes
 // the scale and the pass that encodes with it.  Rows of 25 to 33 vectors per lane keep their last 9 vectors
@@ -155,6 +158,73 @@ __global__ __launch_bounds__(kRowThreads) void fp8_quantize_row_kernel(const T* 
   if (d.slow) encode(std::true_type{}); else encode(std::false_type{});
 }
 
+// ---- dequantise, burst form ------------------------------------------------------------------------------------
+// out[n, v] = decode(code[n, v]) * scale[n].  One workgroup of 1,024 threads per row; every lane loads all of its
+// code chunks (N codes each, N = elements of a 16-byte output vector), decodes them into output vectors held in
+// registers, and only then issues all of its stores: the long same-direction bursts that a read+write stream needs
+// on this device (see dlogits_burst_kernel).  Rows wider than NV * 1,024 vectors take NSEG such bursts, one after
+// the other.  Vectors 0 .. KFULL - 1 of every lane are certain to exist.
+template <typename T, int NV, int NSEG, int KFULL>
+__global__ __launch_bounds__(kRowThreads) void fp8_dequantize_burst_kernel(const unsigned char* __restrict__ codes,
+                                                                           long long codes_stride,
+                                                                           const float* __restrict__ scale, int vocab,
+                                                                           T* __restrict__ out, long long out_stride) {
+  constexpr int N = Vec<T>::N;
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  const long long row = blockIdx.x;
+  const int tid = threadIdx.x;
+  const unsigned char* cr = codes + row * codes_stride;
+  T* orow = out + row * out_stride;
+  u32x4* ov = reinterpret_cast<u32x4*>(orow);
+  const float s = scale[row];
+  const int nvec = vocab / N;
+  const int tail = vocab - nvec * N;
+#pragma unroll
+  for (int seg = 0; seg < NSEG; ++seg) {
+    uint32_t w[NV][N / 4];
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int i = tid + (seg * NV + k) * kRowThreads;
+      if (seg * NV + k < KFULL || i < nvec) {
+        if (N == 8) {
+          const u32x2 c = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(cr + (long long)i * N));
+          w[k][0] = c[0];
+          w[k][N / 4 - 1] = c[1];
+        } else {
+          w[k][0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(cr + (long long)i * N));
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < N / 4; ++j) w[k][j] = 0u;
+      }
+    }
+    u32x4 q[NV];
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {                // in order of arrival
+      float x[N];
+#pragma unroll
+      for (int j = 0; j < N / 4; ++j) {
+        const f32x2v lo = from_e4m3x2(w[k][j] & 0xffffu), hi = from_e4m3x2(w[k][j] >> 16);
+        x[4 * j] = lo[0] * s;
+        x[4 * j + 1] = lo[1] * s;
+        x[4 * j + 2] = hi[0] * s;
+        x[4 * j + 3] = hi[1] * s;
+      }
+      q[k] = Vec<T>::pack(x);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // every vector is made opaque here: no store can be issued before the last load has returned
+#pragma unroll
+    for (int k = 0; k < NV; ++k) asm volatile("" : "+v"(q[k]));
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int i = tid + (seg * NV + k) * kRowThreads;
+      if (seg * NV + k < KFULL || i < nvec) store_stream(ov + i, q[k]);
+    }
+  }
+  if (tid < tail) Vec<T>::store1(orow + nvec * N + tid, from_e4m3x2(cr[nvec * N + tid])[0] * s);
+}
+
 template <typename T>
 int vectors_per_lane(const void* z, int vocab, long long row_stride) {
   constexpr int N = Vec<T>::N;
@@ -221,6 +291,40 @@ bool try_fp8_quantize_rows(ais_ctx* ctx, const void* logits, ais_dtype dtype, lo
   if (need == 0) return false;
   return dispatch_rows<float>(ctx, need, static_cast<const float*>(logits), n_rows, vocab, row_stride, codes,
                               codes_stride, scale_out);
+}
+
+// Returns true when the burst kernel was launched, false when the rows do not qualify (alignment, or wider than
+// 48 output vectors per lane); the caller then runs the streaming kernel.
+bool try_fp8_dequantize_burst(ais_ctx* ctx, const unsigned char* codes, long long codes_stride, const float* scale,
+                              long long n_rows, int vocab, void* out, ais_dtype dtype, long long out_stride) {
+  const int esize = dtype == AIS_BF16 ? 2 : 4;
+  const int n = 16 / esize;                          // elements of an output vector = codes of a chunk
+  if (reinterpret_cast<uintptr_t>(out) % 16 != 0 || (out_stride * esize) % 16 != 0) return false;
+  if (reinterpret_cast<uintptr_t>(codes) % n != 0 || codes_stride % n != 0) return false;
+  const int need = (vocab / n + kRowThreads - 1) / kRowThreads;
+  dim3 grid((unsigned)n_rows), block(kRowThreads);
+  // (vectors that surely exist, vectors per lane and burst, bursts): a row reaches a class only if it is wider than
+  // the class before it
+#define AIS_DEQ_CASE(KFULL, NVAL, NSEG)                                                                        \
+  if (need <= NVAL * NSEG) {                                                                                   \
+    if (dtype == AIS_BF16)                                                                                     \
+      fp8_dequantize_burst_kernel<bf16_t, NVAL, NSEG, KFULL><<<grid, block, 0, ctx->stream>>>(                 \
+          codes, codes_stride, scale, vocab, static_cast<bf16_t*>(out), out_stride);                           \
+    else                                                                                                       \
+      fp8_dequantize_burst_kernel<float, NVAL, NSEG, KFULL><<<grid, block, 0, ctx->stream>>>(                  \
+          codes, codes_stride, scale, vocab, static_cast<float*>(out), out_stride);                            \
+    return true;                                                                                               \
+  }
+  AIS_DEQ_CASE(0, 4, 1)
+  AIS_DEQ_CASE(4, 8, 1)
+  AIS_DEQ_CASE(8, 12, 1)
+  AIS_DEQ_CASE(12, 16, 1)
+  AIS_DEQ_CASE(16, 19, 1)
+  AIS_DEQ_CASE(19, 20, 1)
+  AIS_DEQ_CASE(20, 16, 2)
+  AIS_DEQ_CASE(32, 16, 3)
+#undef AIS_DEQ_CASE
+  return false;
 }
 
 }  // namespace ais

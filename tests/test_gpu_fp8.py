@@ -72,10 +72,14 @@ def test_random_rows(ctx, dtype, vocab):
     assert np.abs(lp.double().cpu().numpy() - ref).max() <= LOGP_ATOL
 
 
-# every instantiation of the register-resident quantise kernel: 4 / 8 / 12 / 16 / 20 / 24 vectors per lane, 18 + 9 and
-# 22 + 9 with the last nine in LDS, and the streaming route beyond (a vector holds 8 bf16 or 4 fp32 elements)
-ROW_VOCABS = {"bf16": [40_001, 90_007, 120_011, 151_936, 190_003, 210_007, 248_320, 260_011, 270_336, 275_003],
-              "f32": [20_011, 45_007, 60_013, 75_011, 95_003, 105_001, 124_003, 130_007, 135_168, 137_501]}
+# every instantiation of the register-resident quantise kernel: 4 / 8 / 12 / 16 / 20 / 24 vectors per lane, 18 + 9,
+# 22 + 9 and 24 + 9 with the last nine in LDS, and the streaming route beyond; and of the burst dequantise kernel:
+# 4 / 8 / 12 / 16 / 19 / 20 vectors per lane in one burst, two and three bursts of 16, and the streaming route beyond
+# 48 (a vector holds 8 bf16 or 4 fp32 elements)
+ROW_VOCABS = {"bf16": [40_001, 90_007, 120_011, 151_936, 160_003, 190_003, 210_007, 248_320, 260_011, 270_336, 275_003,
+                       400_003],
+              "f32": [20_011, 45_007, 60_013, 75_011, 80_021, 95_003, 105_001, 124_003, 130_007, 135_168, 137_501,
+                      200_003]}
 
 
 @pytest.mark.parametrize("dtype,vocab", [(d, v) for d in ("bf16", "f32") for v in ROW_VOCABS[d]])
