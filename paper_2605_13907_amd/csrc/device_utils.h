@@ -13,7 +13,12 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef uint16_t bf16_t;   // raw storage of a bfloat16
 
-constexpr float kNegHuge = -3.0e38f;   // finite stand-in for -inf: keeps (max - max) free of NaN
+constexpr float kNegHuge = -3.0e38f;   // initial running maximum: a finite stand-in for -inf keeps (max - max) free of NaN
+// Value of an element that is excluded from a soft-max sum (the sampled token's own term, positions past the end of a
+// row): it never raises a maximum above the finite running one and adds exactly 2^(-inf) = 0.  A huge finite value
+// would not do: for a lane that has seen nothing else the new maximum is the rounded product x * scale, the fma that
+// forms x * scale - max keeps the product exact, and what is left of that rounding is astronomically large there.
+constexpr float kMasked = -__builtin_inff();
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float log2_fast(float x) { return __builtin_amdgcn_logf(x); }

@@ -144,6 +144,9 @@ __global__ __launch_bounds__(kSweepThreads) void fp8_rollout_logprob_kernel(
   const RowDivider d = make_divider(s);
   const int nvec = VEC ? vocab / N : 0;
   MaxSum st{kNegHuge, 0.f};
+  // the round-tripped logit is s * decode(code): the row scale is folded into the exponent's multiplier (s > 0,
+  // so the running maximum can be taken over the decoded values)
+  const float scale = s * kLog2e;
   auto sweep = [&](auto slow) {
     constexpr bool SLOW = decltype(slow)::value;
     if (VEC) {
@@ -154,15 +157,15 @@ __global__ __launch_bounds__(kSweepThreads) void fp8_rollout_logprob_kernel(
 #pragma unroll
         for (int k = 0; k < N; k += 2) {
           const f32x2v r = from_e4m3x2(to_e4m3x2(divide<SLOW>(x[k], d), divide<SLOW>(x[k + 1], d)));
-          x[k] = r[0] * s;
-          x[k + 1] = r[1] * s;
+          x[k] = r[0];
+          x[k + 1] = r[1];
         }
-        accumulate<N>(x, kLog2e, st);
+        accumulate<N>(x, scale, st);
       }
     }
     for (int v = nvec * N + tid; v < vocab; v += kSweepThreads) {
-      float x = from_e4m3x2(to_e4m3x2(divide<SLOW>(Vec<T>::load1(zr + v), d), 0.f))[0] * s;
-      accumulate<1>(&x, kLog2e, st);
+      float x = from_e4m3x2(to_e4m3x2(divide<SLOW>(Vec<T>::load1(zr + v), d), 0.f))[0];
+      accumulate<1>(&x, scale, st);
     }
   };
   if (d.slow) sweep(std::true_type{}); else sweep(std::false_type{});

@@ -6,8 +6,9 @@
 // the scale and the pass that encodes with it.  Rows of 25 to 33 vectors per lane keep their last 9 vectors
 // per lane in LDS, filled by direct global -> LDS copies.  Same results as the streaming two-pass kernel in
 // fp8.hip, which remains the route for rows that do not fit or are not 16-byte aligned.  (The fused rollout log-prob
-// stays a streaming kernel: its second pass is bound by arithmetic, and a workgroup that owns a whole compute
-// unit cannot overlap that arithmetic with another row's loads; measured slower than two streaming passes.)
+// stays a streaming kernel: its second pass costs 18 vector instructions per element, about 18 us per row on one
+// compute unit, and a workgroup that owns the whole unit cannot overlap that arithmetic with another row's loads:
+// the register-resident form took 4.6 ms on 41,643 rows of 151,936 where two streaming passes take 3.6 ms.)
 #include "ais_internal.h"
 #include "device_utils.h"
 #include "fp8_utils.h"

@@ -26,28 +26,29 @@ using namespace dev;
 constexpr int kRowThreads = 1024;
 constexpr int kRowWaves = kRowThreads / 64;
 
-template <typename T> __device__ __forceinline__ u32x4 lowest_fill();
-template <> __device__ __forceinline__ u32x4 lowest_fill<bf16_t>() {
-  return u32x4{0xff7fff7fu, 0xff7fff7fu, 0xff7fff7fu, 0xff7fff7fu};   // pairs of the most negative finite bf16
+// A vector of excluded elements (-inf in the row's type), for lanes past the end of the row.
+template <typename T> __device__ __forceinline__ u32x4 masked_fill();
+template <> __device__ __forceinline__ u32x4 masked_fill<bf16_t>() {
+  return u32x4{0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u};
 }
-template <> __device__ __forceinline__ u32x4 lowest_fill<float>() {
-  return u32x4{0xff7fffffu, 0xff7fffffu, 0xff7fffffu, 0xff7fffffu};   // -FLT_MAX
+template <> __device__ __forceinline__ u32x4 masked_fill<float>() {
+  return u32x4{0xff800000u, 0xff800000u, 0xff800000u, 0xff800000u};
 }
 
-// q with its element `sub` replaced by the most negative finite value of the type.
-template <typename T> __device__ __forceinline__ u32x4 patch_lowest(u32x4 q, int sub);
-template <> __device__ __forceinline__ u32x4 patch_lowest<bf16_t>(u32x4 q, int sub) {
+// q with its element `sub` excluded (replaced by -inf in the row's type).
+template <typename T> __device__ __forceinline__ u32x4 patch_masked(u32x4 q, int sub);
+template <> __device__ __forceinline__ u32x4 patch_masked<bf16_t>(u32x4 q, int sub) {
   const uint32_t keep = (sub & 1) ? 0x0000ffffu : 0xffff0000u;
-  const uint32_t put = (sub & 1) ? 0xff7f0000u : 0x0000ff7fu;
+  const uint32_t put = (sub & 1) ? 0xff800000u : 0x0000ff80u;
 #pragma unroll
   for (int w = 0; w < 4; ++w)
     if (w == (sub >> 1)) q[w] = (q[w] & keep) | put;
   return q;
 }
-template <> __device__ __forceinline__ u32x4 patch_lowest<float>(u32x4 q, int sub) {
+template <> __device__ __forceinline__ u32x4 patch_masked<float>(u32x4 q, int sub) {
 #pragma unroll
   for (int w = 0; w < 4; ++w)
-    if (w == sub) q[w] = 0xff7fffffu;
+    if (w == sub) q[w] = 0xff800000u;
   return q;
 }
 
@@ -99,7 +100,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
   for (int k = 0; k < NV; ++k) {
     const int i = tid + k * kRowThreads;
     if (k < KFULL) q[k] = load_stream(zv + i);       // the launcher promises nvec > KFULL * kRowThreads
-    else q[k] = (i < nvec) ? load_stream(zv + i) : lowest_fill<T>();
+    else q[k] = (i < nvec) ? load_stream(zv + i) : masked_fill<T>();
   }
   // the LDS slots: lane i of a wavefront deposits its 16 bytes at the wavefront's base + 16 i, which is the
   // slot layout; lanes past the end of the row re-read its last vector (a valid address) and are masked later
@@ -114,7 +115,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
       __builtin_amdgcn_sched_barrier(0);
     }
   }
-  float xt = (tid < tail) ? Vec<T>::load1(zr + nvec * N + tid) : kNegHuge;   // kNegHuge contributes 0
+  float xt = (tid < tail) ? Vec<T>::load1(zr + nvec * N + tid) : kMasked;
 
   const float scale = inv_temperature * kLog2e;
   const int y = token_ids[row];
@@ -127,14 +128,14 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
   const bool y_in_tail = y_ok && y >= nvec * N && (y - nvec * N) == tid;
 
   // The sampled token's own term is kept out of the running sum (see token_logprob_kernel).  Its element
-  // is overwritten, in the packed registers, by the most negative finite value: one lane of one wavefront
-  // takes this branch, the sweeps below stay free of control flow.
+  // is overwritten, in the packed registers, by -inf: one lane of one wavefront takes this branch, the sweeps
+  // below stay free of control flow.
   if (yk >= 0 && yk < NV) {
 #pragma unroll
     for (int k = 0; k < NV; ++k)
-      if (k == yk) q[k] = patch_lowest<T>(q[k], ysub);
+      if (k == yk) q[k] = patch_masked<T>(q[k], ysub);
   }
-  if (y_in_tail) xt = kNegHuge;
+  if (y_in_tail) xt = kMasked;
 
   // ---- phase 1: running (max, sum) over the row, one vector at a time ----
   MaxSum st{kNegHuge, 0.f};
@@ -149,7 +150,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the copies into the slots have landed
     if (yk >= NV) {                                        // the sampled token lies in a slot of this lane
       u32x4* p = lrow + (yk - NV) * kRowThreads + tid;
-      *p = patch_lowest<T>(*p, ysub);
+      *p = patch_masked<T>(*p, ysub);
     }
     int tid1 = tid;
     asm volatile("" : "+v"(tid1));
@@ -163,7 +164,7 @@ __global__ __launch_bounds__(kRowThreads) void fused_logprob_softmax_kernel(
       Vec<T>::unpack(v, x);
       if (NV + k >= KFULL) {
 #pragma unroll
-        for (int j = 0; j < N; ++j) x[j] = (i < nvec) ? x[j] : kNegHuge;
+        for (int j = 0; j < N; ++j) x[j] = (i < nvec) ? x[j] : kMasked;
       }
       accumulate<N>(x, scale, st);
       __builtin_amdgcn_sched_barrier(0);

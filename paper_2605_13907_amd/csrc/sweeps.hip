@@ -67,7 +67,7 @@ __global__ __launch_bounds__(kSweepThreads) void token_logprob_kernel(
         const int hit = ((yvec - i) / kSweepThreads) * N + ysub;
 #pragma unroll
         for (int k = 0; k < UNROLL * N; ++k)
-          if (k == hit) x[k] = kNegHuge;
+          if (k == hit) x[k] = kMasked;
       }
       accumulate<UNROLL * N>(x, scale, st);
     }
@@ -77,13 +77,13 @@ __global__ __launch_bounds__(kSweepThreads) void token_logprob_kernel(
       if (i == yvec) {
 #pragma unroll
         for (int k = 0; k < N; ++k)
-          if (k == ysub) x[k] = kNegHuge;
+          if (k == ysub) x[k] = kMasked;
       }
       accumulate<N>(x, scale, st);
     }
   }
   for (int v = nvec * N + tid; v < vocab; v += kSweepThreads) {   // ragged tail, or the whole row when !VEC
-    float x = (y_ok && v == y) ? kNegHuge : Vec<T>::load1(zr + v);
+    float x = (y_ok && v == y) ? kMasked : Vec<T>::load1(zr + v);
     accumulate<1>(&x, scale, st);
   }
 

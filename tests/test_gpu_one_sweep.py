@@ -89,6 +89,20 @@ def test_wide_bf16_rows(ctx, vocab):
     check_one_sweep(ctx, batch)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("vocab", [1, 5, 7, 264, 1003, 9001])
+@pytest.mark.parametrize("inv_t", [0.3, 0.6])
+def test_high_temperature_short_rows(ctx, vocab, dtype, inv_t):
+    """Temperatures above 1 on rows so short that most lanes hold nothing but excluded elements (positions past
+    the end of the row, the sampled token's own term): those must add exactly 0 whatever the multiplier inside the
+    exponent."""
+    shape = W.RolloutShape("hot", n_prompts=2, group_size=4, vocab=vocab, logits_dtype=dtype, sigma=2.5, boost=4.0,
+                           layout="padded", max_len=9, length_dist=("uniform", 3, 9), reward_p=0.5, seed=vocab + 17)
+    batch = W.generate(shape, "cuda")
+    batch.rewards[:] = torch.tensor([1, 0, 0, 1, 0, 0, 1, 0], dtype=torch.float32)
+    check_one_sweep(ctx, batch, p=B.default_params(inv_temperature=inv_t))
+
+
 def test_pitch_misalignment_and_in_place(ctx):
     shape = W.RolloutShape("pitch", n_prompts=1, group_size=4, vocab=3003, logits_dtype="bf16", sigma=3.0, boost=0.0,
                            layout="packed", max_len=30, length_dist=("uniform", 5, 30), reward_p=0.5, seed=7)

@@ -198,6 +198,41 @@ def test_vocabulary_masked_with_minus_infinity(ctx, dtype):
     assert abs(float(out["logp"][3])) < 1e-6
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("vocab", [1, 5, 7, 264, 1003])
+@pytest.mark.parametrize("inv_t", [0.3, 0.6])
+def test_high_temperature_short_rows(ctx, vocab, dtype, inv_t):
+    """Temperatures above 1 (a multiplier below 1 inside the exponent) on rows so short that most lanes see nothing
+    but excluded elements, and whose sampled token often sits in the scalar tail: an excluded element must add
+    exactly 0 whatever the multiplier."""
+    shape = W.RolloutShape("hot", n_prompts=2, group_size=4, vocab=vocab, logits_dtype=dtype, sigma=2.5, boost=4.0,
+                           layout="padded", max_len=9, length_dist=("uniform", 3, 9), reward_p=0.5, seed=vocab + 17)
+    batch = gen(shape)
+    batch.rewards[:] = torch.tensor([1, 0, 0, 1, 0, 0, 1, 0], dtype=torch.float32)
+    out, ref, d = P.check(ctx, batch, B.default_params(inv_temperature=inv_t))
+    assert torch.isfinite(out["logp"]).all() and torch.isfinite(out["dlogits"].float()).all()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_sampled_token_among_banned_neighbours(ctx, dtype):
+    """Every row keeps only its sampled token and one other entry; everything else, the sampled token's whole
+    16-byte vector included, is -inf.  With a temperature of 2 the lane that holds the sampled token sees nothing
+    but excluded and banned elements."""
+    shape = dataclasses_replace(W.config(2).scaled(vocab=4_107, len_div=64, seed=78), logits_dtype=dtype)
+    batch = gen(shape)
+    R, V = batch.logits.shape
+    y = batch.token_ids.long().clamp(min=0)
+    other = (y + 1777) % V
+    keep = torch.zeros(R, V, dtype=torch.bool, device="cuda")
+    rows = torch.arange(R, device="cuda")
+    keep[rows, y] = True
+    keep[rows, other] = True
+    batch.logits[~keep] = float("-inf")
+    out, ref, d = P.check(ctx, batch, B.default_params(inv_temperature=0.5))
+    assert torch.isfinite(out["logp"]).all() and torch.isfinite(out["dlogits"].float()).all()
+    assert bool((out["dlogits"][~keep] == 0).all())
+
+
 @pytest.mark.parametrize("dtype,factor", [("bf16", 1000.0), ("f32", 3000.0)])
 def test_extreme_logit_magnitudes(ctx, dtype, factor):
     """Logits thousands of units apart: the soft-max is one-hot to working precision, lse is of order 1e4, and
