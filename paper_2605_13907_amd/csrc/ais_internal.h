@@ -21,6 +21,8 @@ constexpr float kLn2 = 0.6931471805599453f;
 struct DiagPartial {
   double su;      // sum of (w_bar - 1)
   double su2;     // sum of (w_bar - 1)^2
+  double sw;      // sum of w_bar
+  double sw2;     // sum of w_bar^2
   double sabs;    // sum of |log pi_train - log pi_roll|
   double sd;      // sum of (log pi_train - log pi_roll)
   double sdp;     // sum of |pi_train - pi_roll|

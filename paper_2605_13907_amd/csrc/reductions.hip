@@ -117,15 +117,17 @@ __device__ void diag_final(const volatile DiagPartial* partial, const int* __res
                            int group_size, const float* __restrict__ rewards, const ais_params& p,
                            float* __restrict__ adv_out, int* __restrict__ count_out, ais_diag* __restrict__ diag_out,
                            const int* __restrict__ status, double* lds_d, long long* lds_i) {
-  double su = 0, su2 = 0, sabs = 0, sd = 0, sdp = 0, sa = 0, sa2 = 0, saw = 0, saw2 = 0;
+  double su = 0, su2 = 0, sw = 0, sw2 = 0, sabs = 0, sd = 0, sdp = 0, sa = 0, sa2 = 0, saw = 0, saw2 = 0;
   long long cnt = 0, nclip = 0;
   for (int i = threadIdx.x; i < n_resp; i += kTileThreads) {
     // fold this response's tiles in order
-    double r_su = 0, r_su2 = 0, r_sabs = 0;
+    double r_su = 0, r_su2 = 0, r_sw = 0, r_sw2 = 0, r_sabs = 0;
     long long r_cnt = 0, r_nclip = 0;
     for (int t = tile_off[i]; t < tile_off[i + 1]; ++t) {
       r_su += partial[t].su;
       r_su2 += partial[t].su2;
+      r_sw += partial[t].sw;
+      r_sw2 += partial[t].sw2;
       r_sabs += partial[t].sabs;
       sd += partial[t].sd;
       sdp += partial[t].sdp;
@@ -151,16 +153,16 @@ __device__ void diag_final(const volatile DiagPartial* partial, const int* __res
     count_out[i] = (int)r_cnt;
     a = (double)a32;                     // the advantage every later step sees is the stored fp32 value
     // token-level moments of A and A w_bar: A is constant over the response's rows
-    const double sw = r_su + (double)r_cnt;                       // sum w_bar
-    const double sw2 = r_su2 + 2.0 * r_su + (double)r_cnt;        // sum w_bar^2
-    su += r_su; su2 += r_su2; sabs += r_sabs; cnt += r_cnt; nclip += r_nclip;
+    su += r_su; su2 += r_su2; sw += r_sw; sw2 += r_sw2; sabs += r_sabs; cnt += r_cnt; nclip += r_nclip;
     sa += a * (double)r_cnt;
     sa2 += a * a * (double)r_cnt;
-    saw += a * sw;
-    saw2 += a * a * sw2;
+    saw += a * r_sw;
+    saw2 += a * a * r_sw2;
   }
   su = block_sum(su, lds_d);
   su2 = block_sum(su2, lds_d);
+  sw = block_sum(sw, lds_d);
+  sw2 = block_sum(sw2, lds_d);
   sabs = block_sum(sabs, lds_d);
   sd = block_sum(sd, lds_d);
   sdp = block_sum(sdp, lds_d);
@@ -182,10 +184,19 @@ __device__ void diag_final(const volatile DiagPartial* partial, const int* __res
     d.alpha = 0.0; d.kl_roll_train = 0.0; d.mean_abs_dp = 0.0;
   } else {
     const double N = (double)cnt;
+    // Two sets of moments: of u = w_bar - 1, which do not cancel when the weights sit near 1 (the usual case), and
+    // of w_bar itself, which keep the mean and the spread when the weights are far below 1 (a trainer that has
+    // drifted by hundreds of nats: 1 + mean(u) would round to 0 there).  Variance is shift-invariant.
     const double mu_u = su / N;
-    d.mean_w = 1.0 + mu_u;
-    d.var_w = fmax(0.0, su2 / N - mu_u * mu_u);               // variance is shift-invariant: var(w_bar) = var(u)
-    d.cv2 = d.var_w / (d.mean_w * d.mean_w);
+    if (1.0 + mu_u >= 0.5) {
+      d.mean_w = 1.0 + mu_u;
+      d.var_w = fmax(0.0, su2 / N - mu_u * mu_u);
+    } else {
+      d.mean_w = sw / N;
+      d.var_w = fmax(0.0, sw2 / N - d.mean_w * d.mean_w);
+    }
+    // every truncated ratio underflowed to 0: CV^2 is 0 / 0; read as 0 (equal weights), like the empty batch
+    d.cv2 = d.mean_w > 0.0 ? d.var_w / (d.mean_w * d.mean_w) : 0.0;
     d.ess_ratio = 1.0 / (1.0 + d.cv2);
     d.alpha_ess = 1.0 / sqrt(1.0 + d.cv2);                    // Eq. 12
     d.dbar = sabs / N;                                        // Eq. 13
@@ -222,15 +233,18 @@ __global__ __launch_bounds__(kTileThreads) void diag_reduce_kernel(
     const long long r0 = lo + (long long)(b - tile_off[i]) * kTileRows;
     const long long r1 = min(hi, r0 + kTileRows);
     const double lnC = log((double)p.C);
-    double su = 0, su2 = 0, sabs = 0, sd = 0, sdp = 0;
+    double su = 0, su2 = 0, sw = 0, sw2 = 0, sabs = 0, sd = 0, sdp = 0;
     long long cnt = 0, nclip = 0;
     for (long long n = r0 + threadIdx.x; n < r1; n += kTileThreads) {
       if (valid != nullptr && valid[n] == 0) continue;
       const double lt = (double)logp_train[n], lr = (double)logp_roll[n];
       const double d = lt - lr;                                            // log rho (Alg. 1, sampler-trainer ratio)
-      const double u = exp(fmin(d, lnC)) - 1.0;                            // w_bar - 1, w_bar = min(rho, C) (Eq. 10)
+      const double w = exp(fmin(d, lnC));                                  // w_bar = min(rho, C) (Eq. 10)
+      const double u = w - 1.0;
       su += u;
       su2 += u * u;
+      sw += w;
+      sw2 += w * w;
       sabs += fabs(d);
       sd += d;
       sdp += fabs(exp(lt) - exp(lr));
@@ -240,6 +254,8 @@ __global__ __launch_bounds__(kTileThreads) void diag_reduce_kernel(
     DiagPartial t;
     t.su = block_sum(su, lds_d);
     t.su2 = block_sum(su2, lds_d);
+    t.sw = block_sum(sw, lds_d);
+    t.sw2 = block_sum(sw2, lds_d);
     t.sabs = block_sum(sabs, lds_d);
     t.sd = block_sum(sd, lds_d);
     t.sdp = block_sum(sdp, lds_d);

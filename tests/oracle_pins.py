@@ -240,6 +240,25 @@ def pin_diag_degenerate(O):
     assert out["n_valid"] == 0 and out["alpha"] == 0.0 and list(out["count"]) == [0, 0]
 
 
+def pin_diag_vanishing_weights(O):
+    """A trainer far below the sampler on every token.  Ratios of 1e-98 are still numbers: CV^2 is scale-invariant,
+    so it equals the CV^2 of the same log-ratios shifted back by a constant (which sit near 1).  Beyond the range of
+    exp every ratio is exactly 0 and CV^2 is 0/0: read as 0, alpha_ess = 1, and nothing is NaN."""
+    lp_roll = RNG.normal(-2, 1, size=12)
+    jitter = RNG.normal(0, 0.3, size=12)
+    cu = np.array([0, 6, 12])
+    adv = np.array([0.5, -0.5])
+    p = O.Params()
+    near = O.diagnostics(lp_roll + jitter - 0.5, lp_roll, None, cu, adv, p)      # ratios around e^-0.5: none truncated
+    far = O.diagnostics(lp_roll + jitter - 225.0, lp_roll, None, cu, adv, p)     # the same ratios times e^-224.5
+    assert far["mean_w"] < 1e-90 and abs(far["cv2"] - near["cv2"]) < 1e-9 * near["cv2"]
+    assert abs(far["alpha_ess"] - near["alpha_ess"]) < 1e-12
+    gone = O.diagnostics(lp_roll + jitter - 2000.0, lp_roll, None, cu, adv, p)
+    assert gone["mean_w"] == 0.0 and gone["cv2"] == 0.0 and gone["alpha_ess"] == 1.0 and gone["ess_ratio"] == 1.0
+    assert gone["alpha_mis"] == 1.0 and gone["alpha"] == 1.0 and all(np.isfinite(float(v)) for k, v in gone.items()
+                                                                      if k != "count")
+
+
 def pin_mismatch_metrics(O):
     """The two logged mismatch metrics (Sec. 3.1, the training-dynamics figure).  Closed form: every token has
     pi_roll = 0.1; half of them pi_train = 0.3, half 0.1  =>  mean(log pi_roll - log pi_train) = -ln(3)/2 and

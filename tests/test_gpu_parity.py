@@ -245,6 +245,25 @@ def test_extreme_logit_magnitudes(ctx, dtype, factor):
     assert torch.isfinite(out["dlogits"].float()).all()
 
 
+@pytest.mark.parametrize("drift", [40.0, 225.0, 2000.0])
+def test_vanishing_weights(ctx, drift):
+    """The trainer puts all of its mass on a token the sampler did not choose, `drift` logit units above the rest:
+    ratios of about 4e-18, 1e-98, and 0 (beyond the range of exp).  Mean and spread of the weights must survive as
+    long as the ratios are numbers, and the 0/0 of the last case is read as CV^2 = 0; alpha stays finite."""
+    shape = W.config(2).scaled(vocab=1032, len_div=64, seed=23)
+    batch = gen(shape)
+    R, V = batch.logits.shape
+    rows = torch.arange(R, device="cuda")
+    other = (batch.token_ids.long().clamp(min=0) + 1) % V
+    batch.logits[rows, other] = batch.logits.float().amax(dim=1).to(batch.logits.dtype) + drift
+    out, ref, d = P.check(ctx, batch)
+    assert np.isfinite(d["alpha"]) and np.isfinite(d["cv2"]) and d["alpha_mis"] == 1.0
+    if drift > 1000:
+        assert d["mean_w"] == 0.0 and d["cv2"] == 0.0 and d["alpha_ess"] == 1.0
+    else:
+        assert 0.0 < d["mean_w"] < 1e-12 and d["cv2"] > 0.0
+
+
 def test_all_ratios_truncated(ctx):
     """rho > C on every token: w_bar == C, CV = 0, alpha_ess = 1, clip_frac = 1."""
     shape = W.config(2).scaled(vocab=1032, len_div=64, seed=21)
