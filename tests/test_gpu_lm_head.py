@@ -82,6 +82,32 @@ def test_shapes(ctx, R, D, V):
     compare(ctx, hidden, weight, y, valid)
 
 
+@pytest.mark.parametrize("seed", range(40))
+def test_random_shapes(ctx, seed):
+    """Seeded random draws of rows, model width (both kernels), vocabulary, mask density, temperature, operand scale
+    and row pitches."""
+    rng = np.random.default_rng(500 + seed)
+    R = int(rng.choice([1, 2, 31, 255, 256, 257, 300, 511, 513, 700, 1025]))
+    D = int(rng.choice([8, 16, 24, 32, 40, 64, 72, 96, 128, 160, 200, 256, 320]))
+    V = int(rng.choice([1, 2, 7, 255, 256, 257, 511, 1000, 2049, 5000, 12_345, 33_333]))
+    p_valid = float(rng.choice([1.0, 0.9, 0.5, 0.1]))
+    inv_t = float(rng.choice([0.3, 0.7, 1.0, 1.0, 1.9]))
+    scale = float(rng.choice([0.05, 1.0, 1.0, 6.0, 40.0]))
+    pad_h, pad_w = int(rng.choice([0, 8, 24])), int(rng.choice([0, 8, 40]))
+    print(f"case {seed}: R={R} D={D} V={V} p_valid={p_valid} inv_t={inv_t} scale={scale} pads={pad_h},{pad_w}", flush=True)
+    hidden, weight, y, valid = make(R, D, V, seed=900 + seed, p_valid=p_valid, scale=scale)
+    if pad_h:
+        hs = torch.full((R, D + pad_h), float("nan"), dtype=torch.bfloat16, device="cuda")
+        hs[:, :D] = hidden
+        hidden = hs[:, :D]
+    if pad_w:
+        ws = torch.full((V, D + pad_w), float("nan"), dtype=torch.bfloat16, device="cuda")
+        ws[:, :D] = weight
+        weight = ws[:, :D]
+    logp, lse = compare(ctx, hidden, weight, y, valid, inv_t)
+    assert torch.isfinite(logp).all() and torch.isfinite(lse).all()
+
+
 @pytest.mark.parametrize("inv_t", [0.5, 1.0, 1.7])
 def test_temperature_and_peaked_rows(ctx, inv_t):
     hidden, weight, y, valid = make(400, 256, 3000, seed=11, scale=4.0)
