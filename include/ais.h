@@ -201,9 +201,9 @@ int ais_grpo_loss_grad(ais_ctx* ctx, const void* logits, ais_dtype dtype, long l
  *
  * ais_token_logprob_softmax_grad: as ais_token_logprob, and additionally
  *   sgrad_out  [n_rows, row_stride] of `dtype`: s on evaluated rows, 0 on the others; may be the same
- *              buffer as `logits` (in place).  Rows are held in the register file of one compute unit
- *              (up to 196,608 bf16 or 98,304 fp32 elements, 16-byte aligned); wider or unaligned rows
- *              are processed in two passes with the same results.
+ *              buffer as `logits` (in place).  Rows are held in the register file and LDS of one compute
+ *              unit (up to 270,336 bf16 or 135,168 fp32 elements, 16-byte aligned); wider or unaligned
+ *              rows are processed in two passes with the same results.
  * ais_grpo_row_scale: as ais_grpo_loss_grad without the logits; writes
  *   g_out      [n_rows] fp32: the derivative of the loss w.r.t. the row's log-probability times
  *              inv_temperature (0 on rows not evaluated or clipped away), so that g_out[n] * s[n, :] equals
