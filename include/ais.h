@@ -92,7 +92,7 @@ typedef struct ais_params {
 typedef struct ais_diag {
   long long n_valid;     /* number of valid rows                                               */
   double mean_w, var_w;  /* mean and population variance of w_bar = min(rho, C)                */
-  double cv2;            /* squared coefficient of variation of w_bar                          */
+  double cv2;            /* squared coefficient of variation of w_bar (0 if every w_bar is 0)  */
   double ess_ratio;      /* 1 / (1 + cv2)                                                      */
   double dbar;           /* mean |log pi_train - log pi_roll|            (Eq. 13)              */
   double std_a, std_aw;  /* population std of A and of A * w_bar                               */
