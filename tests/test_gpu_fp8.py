@@ -94,6 +94,35 @@ def test_every_row_width_class(ctx, dtype, vocab):
     check_quant(ctx, z)
 
 
+@pytest.mark.parametrize("seed", range(30))
+def test_random_rows_wide_dynamic_range(ctx, seed):
+    """Seeded random draws: width, dtype, and per row a magnitude between 1e-30 and 1e30, a share of exact zeros and
+    of values many orders below the row's abs-max (the bottom of the E4M3 grid and its subnormals), -0, and one row
+    with a single non-zero entry; optionally a padded pitch.  Codes and scales bit-exact."""
+    rng = np.random.default_rng(7000 + seed)
+    vocab = int(rng.choice([1, 3, 8, 9, 255, 1000, 1025, 4097, 8200, 20_481, 33_001, 66_000, 151_936, 248_320]))
+    dt = torch.bfloat16 if rng.random() < 0.5 else torch.float32
+    R = 6 if vocab > 60_000 else 24
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    z = torch.randn(R, vocab, generator=g)
+    mag = torch.from_numpy(10.0 ** rng.uniform(-30, 30, size=(R, 1))).float()
+    small = torch.from_numpy(10.0 ** rng.uniform(-8, 0, size=(R, vocab))).float()
+    z = z * torch.where(torch.rand(R, vocab, generator=g) < 0.5, small, torch.ones_like(small)) * mag
+    z[torch.rand(R, vocab, generator=g) < 0.1] = 0.0
+    z[torch.rand(R, vocab, generator=g) < 0.02] = -0.0
+    z[0] = 0.0
+    z[0, vocab // 2] = -3.0e-20                       # a single non-zero entry, and a tiny one
+    pad = int(rng.choice([0, 0, 8, 24]))
+    zc = z.to(dt).cuda()
+    if pad:
+        wide = torch.full((R, vocab + pad), float("nan"), dtype=dt, device="cuda")
+        wide[:, :vocab] = zc
+        zc = wide[:, :vocab]
+    print(f"case {seed}: vocab={vocab} dtype={dt} pad={pad}", flush=True)
+    check_quant(ctx, zc)
+
+
 def all_ones_scale_absmax():
     """An fp32 abs-max whose scale RN(amax / 448) has an all-ones significand (the divisor the reciprocal
     scheme must hand to the true division), found by search on the CPU."""
