@@ -22,7 +22,13 @@
  *   Order      Calls enqueue work on the context's HIP stream and return
  *              without waiting for it.  Results are ready when that stream
  *              reaches the point of the call.  Calls on one context must not
- *              overlap in time (they share its workspace).
+ *              overlap in time (they share its workspace); different contexts
+ *              are independent.
+ *   Workspace  The workspace grows when a call needs more than any call before
+ *              it (more rows or responses): that call waits for the stream and
+ *              allocates device memory.  Calls at sizes seen before allocate
+ *              nothing and can be recorded into a HIP graph; run one call at
+ *              the largest size before capturing.
  *   Layout     Logits are row-major [n_rows, vocab] with a row pitch of
  *              row_stride elements.  One row is one token position.  Response
  *              i owns rows [cu_rows[i], cu_rows[i+1]); cu_rows[0] = 0,
