@@ -161,7 +161,8 @@ def diagnostics(logp_train, logp_roll, valid, cu_rows, adv, p: Params):
     alpha_mis = min(1.0, dbar / p.delta)            # Eq. 14
     std_a = a.std()
     std_aw = (a * w).std()
-    dsigma = std_aw / (std_a + p.eps_std)           # Eq. 15
+    # Eq. 15; with eps_std = 0 and all advantages equal the ratio is 0 / 0: nothing to amplify, read as 0
+    dsigma = std_aw / (std_a + p.eps_std) if std_a + p.eps_std > 0.0 else 0.0
     alpha_var = max(0.0, (dsigma - p.gamma) / p.gamma)          # Eq. 16
     alpha = min(1.0, max(0.0, alpha_ess - p.beta_var * alpha_var)) * alpha_mis   # Eq. 17
     if p.alpha_override >= 0:

@@ -204,7 +204,9 @@ __device__ void diag_final(const volatile DiagPartial* partial, const int* __res
     const double ma = sa / N, maw = saw / N;
     d.std_a = sqrt(fmax(0.0, sa2 / N - ma * ma));
     d.std_aw = sqrt(fmax(0.0, saw2 / N - maw * maw));
-    d.dsigma = d.std_aw / (d.std_a + (double)p.eps_std);      // Eq. 15
+    // Eq. 15; with eps_std = 0 and all advantages equal the ratio is 0 / 0: nothing to amplify, read as 0
+    const double den = d.std_a + (double)p.eps_std;
+    d.dsigma = den > 0.0 ? d.std_aw / den : 0.0;
     d.alpha_var = fmax(0.0, (d.dsigma - (double)p.gamma) / (double)p.gamma);   // Eq. 16
     const double rel = fmin(1.0, fmax(0.0, d.alpha_ess - (double)p.beta_var * d.alpha_var));
     d.alpha = rel * d.alpha_mis;                              // Eq. 17

@@ -238,6 +238,11 @@ def pin_diag_degenerate(O):
     assert abs(out["alpha"] - 1.0) < 1e-12          # constant ratio: CV = 0
     out = O.diagnostics(lp, lp, np.zeros(10, dtype=bool), cu, np.array([0.5, -0.5]), p)
     assert out["n_valid"] == 0 and out["alpha"] == 0.0 and list(out["count"]) == [0, 0]
+    # eps_std = 0 and all advantages equal: Delta-sigma is 0/0, read as 0 (nothing to amplify), alpha stays finite
+    import dataclasses
+    p0 = dataclasses.replace(p, eps_std=0.0)
+    out = O.diagnostics(lp + 0.3, lp, None, cu, np.array([0.0, 0.0]), p0)
+    assert out["dsigma"] == 0.0 and out["alpha_var"] == 0.0 and abs(out["alpha"] - 1.0) < 1e-12
 
 
 def pin_diag_vanishing_weights(O):

@@ -113,7 +113,8 @@ def compare_scalars(ctx, out, ref, batch):
         mean_w, var_w = rd["mean_w"], rd["var_w"]
         t_var = 4.0 * (np.sqrt(var_w) * Ew + Ew * Ew)
         t_cv2 = (t_var + 2.0 * var_w * Ew / max(mean_w, 1e-300)) / max(mean_w * mean_w, 1e-300) if mean_w > 0 else 0.0
-        t_dsig = 2.0 * a_max * Ew / (rd["std_a"] + op.eps_std)
+        den = rd["std_a"] + op.eps_std
+        t_dsig = 2.0 * a_max * Ew / den if den > 0 else 0.0
         extra = dict(mean_w=Ew, var_w=t_var, cv2=t_cv2, ess_ratio=t_cv2, alpha_ess=t_cv2, dbar=E, std_a=0.0,
                      std_aw=2.0 * a_max * Ew, dsigma=t_dsig, alpha_mis=E / op.delta, clip_frac=0.0, mean_abs_dp=E)
         for k in ("mean_w", "var_w", "cv2", "ess_ratio", "dbar", "std_a", "std_aw", "dsigma", "alpha_ess", "alpha_mis",

@@ -264,6 +264,17 @@ def test_vanishing_weights(ctx, drift):
         assert 0.0 < d["mean_w"] < 1e-12 and d["cv2"] > 0.0
 
 
+def test_zero_stabiliser_and_equal_rewards(ctx):
+    """eps_std = 0 with every reward equal: Delta-sigma is 0/0 and is read as 0; alpha, loss and gradient stay
+    finite (the gradient is exactly 0: every advantage is 0)."""
+    shape = W.config(2).scaled(vocab=1032, len_div=64, seed=25)
+    batch = gen(shape)
+    batch.rewards[:] = 1.0
+    out, ref, d = P.check(ctx, batch, B.default_params(eps_std=0.0))
+    assert d["dsigma"] == 0.0 and d["alpha_var"] == 0.0 and np.isfinite(d["alpha"])
+    assert float(out["loss"].item()) == 0.0 and not bool(out["dlogits"].any())
+
+
 def test_all_ratios_truncated(ctx):
     """rho > C on every token: w_bar == C, CV = 0, alpha_ess = 1, clip_frac = 1."""
     shape = W.config(2).scaled(vocab=1032, len_div=64, seed=21)

@@ -32,8 +32,9 @@ MUTANTS = [
     ("dbar = np.abs(d[valid]).mean()", "dbar = np.abs(d[valid].mean())"),
     ("dbar = np.abs(d[valid]).mean()", "dbar = np.abs(rho[valid] - 1).mean()"),
     ("alpha_mis = min(1.0, dbar / p.delta)", "alpha_mis = min(1.0, dbar * p.delta)"),
-    ("dsigma = std_aw / (std_a + p.eps_std)", "dsigma = std_a / (std_aw + p.eps_std)"),
-    ("dsigma = std_aw / (std_a + p.eps_std)", "dsigma = std_aw / std_a if std_a else 0.0"),
+    ("dsigma = std_aw / (std_a + p.eps_std) if", "dsigma = std_a / (std_aw + p.eps_std) if"),
+    ("dsigma = std_aw / (std_a + p.eps_std) if std_a + p.eps_std > 0.0 else 0.0", "dsigma = std_aw / std_a if std_a else 0.0"),
+    ("if std_a + p.eps_std > 0.0 else 0.0", "if std_a + p.eps_std > 0.0 else 1e9"),
     ("alpha_var = max(0.0, (dsigma - p.gamma) / p.gamma)", "alpha_var = max(0.0, dsigma - p.gamma)"),
     ("alpha_ess - p.beta_var * alpha_var", "alpha_ess + p.beta_var * alpha_var"),
     ("alpha_ess - p.beta_var * alpha_var", "alpha_ess - alpha_var"),
