@@ -30,6 +30,8 @@ Readings where the paper is silent:
     k3 form exp(q) - q - 1 with q = log pi_ref - log pi_theta, averaged like the surrogate.
     Parity unpinned by the paper for that term (pinned here only by its own closed forms).
   * temperature: logits are multiplied by inv_temperature before the softmax.
+  * quotients that are 0 / 0 for degenerate batches are read as 0: CV^2 when every truncated ratio is exactly 0,
+    Delta-sigma and the normalised advantage when eps_std = 0 and the advantages (rewards of a group) are all equal.
 
 Parity pins for every function are in tests/oracle_pins.py; numeric values of alpha
 for a given input are not printed anywhere in the paper, so they are pinned by closed
@@ -110,7 +112,9 @@ def group_advantages(rewards, group_size: int, adv_mode: int = 0, eps_std: float
     g = r.reshape(-1, group_size)
     adv = g - g.mean(axis=1, keepdims=True)
     if adv_mode == 1:
-        adv = adv / (g.std(axis=1, keepdims=True) + eps_std)
+        den = g.std(axis=1, keepdims=True) + eps_std
+        # eps_std = 0 and a group with equal rewards: 0 / 0, read as 0 (the numerator is exactly 0)
+        adv = np.where(den > 0.0, adv / np.where(den > 0.0, den, 1.0), 0.0)
     return adv.reshape(-1)
 
 

@@ -146,7 +146,8 @@ __device__ void diag_final(const volatile DiagPartial* partial, const int* __res
         const double e = (double)rewards[g0 + j] - mean;
         var += e * e;
       }
-      a /= sqrt(var / group_size) + (double)p.eps_std;
+      const double den = sqrt(var / group_size) + (double)p.eps_std;
+      a = den > 0.0 ? a / den : 0.0;     // eps_std = 0 and equal rewards: 0 / 0, read as 0
     }
     const float a32 = (float)a;
     adv_out[i] = a32;

@@ -123,6 +123,9 @@ def pin_advantages(O):
     np.testing.assert_allclose(a2[:8], r2[:8] - r2[:8].mean(), atol=1e-15)
     a3 = O.group_advantages(r2, 8, adv_mode=1, eps_std=0.0)
     np.testing.assert_allclose(a3.reshape(3, 8).std(axis=1), 1.0, atol=1e-12)
+    # eps_std = 0 and a group whose rewards are all equal: 0/0 is read as 0, the other group is unaffected
+    a4 = O.group_advantages(r, 6, adv_mode=1, eps_std=0.0)
+    assert np.all(a4[6:] == 0) and np.all(np.isfinite(a4)) and abs(a4[:6].std() - 1.0) < 1e-12
 
 
 # --------------------------------------------------------------------------- O4

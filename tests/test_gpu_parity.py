@@ -273,6 +273,9 @@ def test_zero_stabiliser_and_equal_rewards(ctx):
     out, ref, d = P.check(ctx, batch, B.default_params(eps_std=0.0))
     assert d["dsigma"] == 0.0 and d["alpha_var"] == 0.0 and np.isfinite(d["alpha"])
     assert float(out["loss"].item()) == 0.0 and not bool(out["dlogits"].any())
+    # normalised advantages: 0 / (0 + 0) per group is read as 0 as well
+    out, ref, d = P.check(ctx, batch, B.default_params(eps_std=0.0, adv_mode=1))
+    assert not bool(out["adv"].any()) and np.isfinite(d["alpha"]) and float(out["loss"].item()) == 0.0
 
 
 def test_all_ratios_truncated(ctx):

@@ -23,6 +23,7 @@ MUTANTS = [
     # O3
     ("g = r.reshape(-1, group_size)", "g = r.reshape(group_size, -1).T"),
     ("adv = g - g.mean(axis=1, keepdims=True)", "adv = g - np.median(g, axis=1, keepdims=True)"),
+    ("adv = np.where(den > 0.0, adv / np.where(den > 0.0, den, 1.0), 0.0)", "adv = adv / (den + 1e-3)"),
     # O4
     ("var_w = ((w - mean_w) ** 2).mean()", "var_w = ((w - mean_w) ** 2).sum() / (w.size - 1)"),
     ("cv2 = var_w / mean_w ** 2", "cv2 = var_w / mean_w"),
