@@ -44,7 +44,7 @@ def draw_case(seed):
                   clip_eps=float(rng.choice([0.0, 0.1, 0.2, 0.5])), adv_mode=int(rng.integers(0, 2)),
                   alpha_override=float(rng.choice([-1.0, -1.0, -1.0, 0.0, 0.37, 1.0])),
                   inv_temperature=float(rng.choice([0.25, 0.6, 1.0, 1.0, 1.0 / 0.9, 2.5])),
-                  beta_kl=float(rng.choice([0.0, 0.0, 0.04, 0.5])))
+                  beta_kl=float(rng.choice([0.0, 0.0, 0.04, 0.5])), eps_std=float(rng.choice([1e-6, 1e-6, 0.0])))
     extras = dict(stale=bool(rng.random() < 0.4), ban=float(rng.choice([0.0, 0.0, 0.3, 0.9])),
                   factor=float(rng.choice([1.0, 1.0, 1.0, 30.0, 0.01])), in_place=bool(rng.random() < 0.3),
                   pad=int(rng.choice([0, 0, 8, 24])), mixed_rewards=bool(rng.random() < 0.8))
