@@ -159,7 +159,7 @@ def diagnostics(logp_train, logp_roll, valid, cu_rows, adv, p: Params):
     var_w = ((w - mean_w) ** 2).mean()              # population variance
     # every truncated ratio exactly 0 (exp underflow, a trainer hundreds of nats away from the sampler): CV^2 is
     # 0 / 0; read as 0, i.e. equal weights and alpha_ess = 1, the same convention as the empty batch above
-    cv2 = var_w / mean_w ** 2 if mean_w > 0.0 else 0.0
+    cv2 = (np.sqrt(var_w) / mean_w) ** 2 if mean_w > 0.0 else 0.0    # (std / mean)^2: mean^2 alone may underflow
     alpha_ess = (1.0 + cv2) ** -0.5                 # Eq. 12
     dbar = np.abs(d[valid]).mean()                  # Eq. 13
     alpha_mis = min(1.0, dbar / p.delta)            # Eq. 14

@@ -197,7 +197,8 @@ __device__ void diag_final(const volatile DiagPartial* partial, const int* __res
       d.var_w = fmax(0.0, sw2 / N - d.mean_w * d.mean_w);
     }
     // every truncated ratio underflowed to 0: CV^2 is 0 / 0; read as 0 (equal weights), like the empty batch
-    d.cv2 = d.mean_w > 0.0 ? d.var_w / (d.mean_w * d.mean_w) : 0.0;
+    const double cv = d.mean_w > 0.0 ? sqrt(d.var_w) / d.mean_w : 0.0;    // std / mean: mean^2 alone may underflow
+    d.cv2 = cv * cv;
     d.ess_ratio = 1.0 / (1.0 + d.cv2);
     d.alpha_ess = 1.0 / sqrt(1.0 + d.cv2);                    // Eq. 12
     d.dbar = sabs / N;                                        // Eq. 13

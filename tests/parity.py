@@ -73,6 +73,12 @@ def run_oracle(batch, p: B.AisParams, logp_old=None, logp_ref=None, row_chunk=25
     lo = None if logp_old is None else to_np64(logp_old)
     lr = None if logp_ref is None else to_np64(logp_ref)
     loss, wtilde, g = O.loss_and_row_coeff(logp, lp_roll, lo, lr, valid, cu, adv, diag["count"], diag["alpha"], op)
+    # how strongly a row's coefficient reacts to its own log-prob through the KL term: d/dlogp of beta_kl (1 - e^q) / (B |o_i|)
+    kl_sens = np.zeros(R)
+    if lr is not None and op.beta_kl > 0:
+        seq = O.rows_to_responses(cu, R)
+        cnt = np.maximum(diag["count"][seq], 1)
+        kl_sens = np.where(valid.astype(bool), op.beta_kl * np.exp(lr - logp) / (len(cu) - 1) / cnt, 0.0)
 
     def dz_chunks():
         for r0 in range(0, R, row_chunk):
@@ -80,7 +86,8 @@ def run_oracle(batch, p: B.AisParams, logp_old=None, logp_ref=None, row_chunk=25
             yield r0, r1, O.dlogits_rows(to_np64(batch.logits[r0:r1]), lse[r0:r1], y[r0:r1], g[r0:r1],
                                          op.inv_temperature)
 
-    return dict(logp=logp, lse=lse, adv=adv, diag=diag, loss=loss, wtilde=wtilde, g=g, dz_chunks=dz_chunks, params=op)
+    return dict(logp=logp, lse=lse, adv=adv, diag=diag, loss=loss, wtilde=wtilde, g=g, dz_chunks=dz_chunks, params=op,
+                kl_sens=kl_sens, g_slack=np.zeros(R))
 
 
 def rel_close(got, ref, rel=REL, floor=0.0, what=""):
@@ -117,8 +124,15 @@ def compare_scalars(ctx, out, ref, batch):
         t_dsig = 2.0 * a_max * Ew / den if den > 0 else 0.0
         extra = dict(mean_w=Ew, var_w=t_var, cv2=t_cv2, ess_ratio=t_cv2, alpha_ess=t_cv2, dbar=E, std_a=0.0,
                      std_aw=2.0 * a_max * Ew, dsigma=t_dsig, alpha_mis=E / op.delta, clip_frac=0.0, mean_abs_dp=E)
+        # weights below 1e-140 have squares at the bottom of the fp64 range: the oracle's own variance is made of
+        # denormals there and says nothing; only finiteness and range are checked for the spread statistics
+        skip = ("var_w", "cv2", "ess_ratio", "alpha_ess") if 0.0 < mean_w < 1e-140 else ()
+        if skip:
+            assert np.isfinite(d["cv2"]) and d["cv2"] >= 0.0 and 0.0 < d["alpha_ess"] <= 1.0
         for k in ("mean_w", "var_w", "cv2", "ess_ratio", "dbar", "std_a", "std_aw", "dsigma", "alpha_ess", "alpha_mis",
                   "clip_frac", "mean_abs_dp"):
+            if k in skip:
+                continue
             # quantities that are exactly 0 in the oracle (e.g. std of all-equal advantages) get a tiny floor
             tol = REL * max(abs(rd[k]), 1e-9) + extra[k]
             assert abs(d[k] - rd[k]) <= tol, f"{k}: gpu {d[k]!r} oracle {rd[k]!r} tol {tol:.3e} (E = {E:.1e})"
@@ -129,7 +143,9 @@ def compare_scalars(ctx, out, ref, batch):
     else:
         t_avar = t_alpha = 0.0
     assert abs(d["alpha_var"] - rd["alpha_var"]) <= REL * max(abs(rd["alpha_var"]), 1e-3) + t_avar, "alpha_var"
-    if op.alpha_override < 0:
+    if op.alpha_override < 0 and rd["n_valid"] > 0 and 0.0 < rd["mean_w"] < 1e-140:
+        assert 0.0 <= d["alpha"] <= 1.0
+    elif op.alpha_override < 0:
         assert abs(d["alpha"] - rd["alpha"]) <= REL * max(abs(rd["alpha"]), 1e-3) + t_alpha, \
             f"alpha: gpu {d['alpha']!r} oracle {rd['alpha']!r}"
     else:
@@ -151,6 +167,9 @@ def compare_scalars(ctx, out, ref, batch):
         f"loss: gpu {float(out['loss'].item())!r} oracle {ref['loss']!r} floor {floor:.3e} E {E:.1e}"
     d["_E"] = E
     d["_t_alpha"] = t_alpha
+    # what E can do to a row's gradient coefficient: through w_tilde and the on-policy ratio (relative), and through
+    # the KL term (absolute, and the whole of it on rows whose advantage is 0 and whose q is close to 0)
+    ref["g_slack"] = np.abs(ref["g"]) * (2.0 * E + Ew + t_alpha * max(1.0, op.C - 1.0)) + ref["kl_sens"] * E
     return d
 
 
@@ -164,6 +183,7 @@ def compare_dlogits(out, ref, batch):
         assert np.all(got[zero_rows] == 0), "rows without gradient must be exactly 0"
         rowmax = np.abs(ref_dz).max(axis=1, keepdims=True)
         tol = DZ_REL * np.abs(ref_dz) + DZ_CUSHION * rowmax + DZ_TINY + oracle_floor(ref["g"][r0:r1], ref["lse"][r0:r1])
+        tol = tol + (ref["g_slack"][r0:r1] * ref["params"].inv_temperature)[:, None]     # see compare_scalars
         err = np.abs(got - ref_dz)
         bad = err > tol
         assert not bad.any(), (f"dlogits mismatch in rows {r0}:{r1}: {int(bad.sum())} elements, worst "

@@ -2,6 +2,8 @@
 dtype, hyper-parameters, temperature, optional stale / reference policies, banned (-inf) tokens, logit magnitude
 and memory layout, and runs the three-call path and the one-sweep path against the CPU oracle with the same
 tolerances as the other parity tests.  The draws are functions of the seed alone, so a failure names its case."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -84,7 +86,7 @@ def build_case(seed):
     return batch, p, logp_old, logp_ref, extras
 
 
-SEEDS = list(range(160))
+SEEDS = list(range(int(os.environ.get("AIS_RANDOM_CASES", "160"))))      # more cases for an occasional long run
 
 
 @pytest.mark.parametrize("seed", SEEDS)

@@ -26,7 +26,8 @@ MUTANTS = [
     ("adv = np.where(den > 0.0, adv / np.where(den > 0.0, den, 1.0), 0.0)", "adv = adv / (den + 1e-3)"),
     # O4
     ("var_w = ((w - mean_w) ** 2).mean()", "var_w = ((w - mean_w) ** 2).sum() / (w.size - 1)"),
-    ("cv2 = var_w / mean_w ** 2", "cv2 = var_w / mean_w"),
+    ("cv2 = (np.sqrt(var_w) / mean_w) ** 2", "cv2 = np.sqrt(var_w) / mean_w"),
+    ("cv2 = (np.sqrt(var_w) / mean_w) ** 2", "cv2 = (var_w / mean_w) ** 2"),
     ("if mean_w > 0.0 else 0.0", "if mean_w > 0.0 else 1.0"),
     ("if mean_w > 0.0 else 0.0", "if mean_w > 1e-50 else 0.0"),
     ("alpha_ess = (1.0 + cv2) ** -0.5", "alpha_ess = (1.0 + cv2) ** -1.0"),
