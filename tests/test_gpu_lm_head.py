@@ -230,3 +230,50 @@ def test_full_size_sampled(ctx):
     rng = np.random.default_rng(5)
     rows = np.unique(np.concatenate([[0, 1, 255, 256, 257, R - 257, R - 256, R - 1], rng.integers(0, R, 40)]))
     compare(ctx, batch.hidden, batch.weight, batch.token_ids, batch.valid, rows=rows)
+
+
+def test_hidden_state_path_end_to_end(ctx):
+    """The path without materialised logits: log-probs from hidden states, then the diagnostics and the per-row
+    gradient coefficient.  The oracle forms the logits in fp64 and runs its own steps on them; what comes out of the
+    three calls (alpha, loss, w_tilde, g) must agree to the tolerances of the logits-based path."""
+    import oracle.ais_oracle as O
+    from tests import parity as P
+    R, D, V, G, n_resp = 640, 128, 3000, 4, 8
+    hidden, weight, y, _ = make(R, D, V, seed=71)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(72)
+    valid = (torch.rand(R, generator=g) < 0.85).to(torch.uint8)
+    cu = torch.arange(n_resp + 1, dtype=torch.int64) * (R // n_resp)
+    rewards = torch.tensor([1, 0, 0, 1, 0, 1, 1, 0], dtype=torch.float32)
+    inv_t = 1.0 / 0.9
+    p = B.default_params(inv_temperature=inv_t, beta_kl=0.04)
+    z = L.logits(f64(hidden), f64(weight))
+    lp_ref, lse_ref = O.token_logprob(z, y.cpu().numpy(), valid.numpy(), inv_t)
+    rng = np.random.default_rng(73)
+    logp_roll = np.where(valid.numpy() != 0, lp_ref + rng.normal(0, 0.05, size=R), 0.0).astype(np.float32)
+    logp_ref_policy = np.where(valid.numpy() != 0, lp_ref + rng.normal(0, 0.1, size=R), 0.0).astype(np.float32)
+    op = P.oracle_params(p)
+    adv_ref = O.group_advantages(rewards.double().numpy(), G, op.adv_mode, op.eps_std)
+    rd = O.diagnostics(lp_ref, logp_roll, valid.numpy(), cu.numpy(), adv_ref, op)
+    loss_ref, wt_ref, g_ref = O.loss_and_row_coeff(lp_ref, logp_roll.astype(np.float64), None,
+                                                   logp_ref_policy.astype(np.float64), valid.numpy(), cu.numpy(),
+                                                   adv_ref, rd["count"], rd["alpha"], op)
+
+    dev = lambda a: torch.from_numpy(a).cuda() if isinstance(a, np.ndarray) else a.cuda()
+    logp, lse = ctx.lm_head_logprob(hidden, weight, y, dev(valid), inv_t)
+    adv, count, diag = ctx.diagnostics(logp, dev(logp_roll), dev(valid), dev(cu), dev(rewards), G, p)
+    loss, wtilde, gcoef = ctx.grpo_row_scale(logp, dev(logp_roll), dev(valid), dev(cu), adv, count, diag, p,
+                                             logp_ref=dev(logp_ref_policy))
+    torch.cuda.synchronize()
+    d = ctx.read_diag(diag)
+    E = float(np.abs(logp.cpu().numpy() - lp_ref).max())
+    print(f"max |dlogp| {E:.2e}", flush=True)
+    assert E <= LOGP_ATOL and ctx.status() == 0
+    assert d["n_valid"] == rd["n_valid"] and count.cpu().tolist() == [int(c) for c in rd["count"]]
+    for k in ("mean_w", "cv2", "dbar", "dsigma", "alpha_ess", "alpha_mis", "alpha"):
+        P.rel_close(d[k], rd[k], floor=1e-6 + 10 * E, what=k)
+    np.testing.assert_allclose(wtilde.cpu().numpy(), wt_ref, rtol=P.REL, atol=1e-6 + 10 * E)
+    np.testing.assert_allclose(gcoef.cpu().numpy(), g_ref * inv_t, rtol=P.REL,
+                               atol=(1e-6 + 10 * E) * float(np.abs(g_ref).max()))
+    scale = float(np.sum(np.abs(adv_ref)) / n_resp) + op.beta_kl
+    assert abs(float(loss.item()) - loss_ref) <= (P.REL + 10 * E) * max(abs(loss_ref), scale)
