@@ -71,7 +71,7 @@ struct DeviceGuard {
 
 int check_logits(const void* logits, ais_dtype dtype, long long n_rows, long long vocab, long long row_stride) {
   if (dtype != AIS_BF16 && dtype != AIS_F32) return AIS_ERR_DTYPE;
-  if (n_rows < 0 || n_rows > 0x7fffffffLL) return AIS_ERR_SIZE;
+  if (n_rows < 0 || n_rows > 0x7fffffffLL - 8) return AIS_ERR_SIZE;   // grids are rounded up to a multiple of 8 rows
   if (vocab < 1 || vocab > 0x7fffffffLL - 8) return AIS_ERR_SIZE;
   if (row_stride < vocab) return AIS_ERR_STRIDE;
   if (n_rows > 0 && logits == nullptr) return AIS_ERR_NULL;
