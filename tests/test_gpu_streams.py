@@ -1,5 +1,6 @@
-"""Two contexts on two streams of one GPU, their calls interleaved from the host: each context owns its workspace,
-so the results must be bit-identical to running the same batches one after the other."""
+"""Contexts and streams.  Two contexts on two streams of one GPU, their calls interleaved from the host: each context
+owns its workspace, so the results must be bit-identical to running the same batches one after the other.  And a
+context that is destroyed gives back everything it allocated."""
 import pytest
 import torch
 
@@ -37,3 +38,33 @@ def test_two_contexts_two_streams():
         assert float(outs[k]["loss"].item()) == float(ref[k]["loss"].item())
         assert ctxs[k].status() == 0
         ctxs[k].close()
+
+
+def test_context_lifetimes_release_their_memory():
+    """Creating a context, running every entry point once and destroying it leaves no device memory behind."""
+    shape = W.config(1)
+    batch = W.generate(shape, "cuda")
+    rb = W.generate_readout(shape, device="cuda")
+    p = B.default_params()
+
+    def one_lifetime():
+        ctx = B.AisContext()
+        ctx.step(batch, p)
+        ctx.step_one_sweep(batch, p)
+        ctx.lm_head_logprob(rb.hidden, rb.weight, rb.token_ids, rb.valid)
+        ctx.profile(True)
+        ctx.step(batch, p)
+        ctx.profile_read(B.AIS_K_LOGPROB)
+        ctx.profile(False)
+        assert ctx.status() == 0
+        ctx.close()
+
+    for _ in range(3):                                            # torch's caching allocator reaches its steady state
+        one_lifetime()
+    torch.cuda.synchronize()
+    free_before = torch.cuda.mem_get_info()[0]
+    for _ in range(100):
+        one_lifetime()
+    torch.cuda.synchronize()
+    free_after = torch.cuda.mem_get_info()[0]
+    assert free_before - free_after < 32 << 20, (free_before, free_after)
