@@ -150,6 +150,118 @@ def test_lm_head_logprob_argument_checks():
     assert call(n_rows=0, hidden=None, tok=None, logp=None, lse=None) == -1
 
 
+def test_one_sweep_argument_checks():
+    lib = B._lib()
+    p = B.default_params()
+
+    def sweep(**kw):
+        a = dict(ctx=None, logits=FAKE, dtype=B.AIS_F32, n_rows=4, vocab=64, stride=72, tok=FAKE, valid=None,
+                 inv_t=1.0, logp=FAKE, lse=FAKE, sgrad=FAKE)
+        a.update(kw)
+        return lib.ais_token_logprob_softmax_grad(a["ctx"], a["logits"], a["dtype"], a["n_rows"], a["vocab"],
+                                                  a["stride"], a["tok"], a["valid"], a["inv_t"], a["logp"],
+                                                  a["lse"], a["sgrad"])
+
+    assert sweep() == -1                                         # everything fine except the NULL context
+    assert sweep(sgrad=None) == -1
+    assert sweep(lse=None) == -1
+    assert sweep(sgrad=C.c_void_p(0x3002)) == -4                 # fp32 output on a 2-byte boundary
+    assert sweep(dtype=B.AIS_BF16, sgrad=C.c_void_p(0x3002)) == -1   # fine for bf16: only the context is missing
+    assert sweep(stride=63) == -3
+    assert sweep(vocab=0) == -2
+    assert sweep(dtype=-1) == -7
+    assert sweep(inv_t=float("inf")) == -5
+    assert sweep(n_rows=0, logits=None, tok=None, logp=None, lse=None, sgrad=None) == -1
+
+    def scale(params=p, **kw):
+        a = dict(ctx=None, lt=FAKE, lr=FAKE, lo=None, lref=None, valid=None, n_rows=10, cu=FAKE, n_resp=8, adv=FAKE,
+                 count=FAKE, diag=FAKE, wt=None, loss=FAKE, g=FAKE)
+        a.update(kw)
+        return lib.ais_grpo_row_scale(a["ctx"], a["lt"], a["lr"], a["lo"], a["lref"], a["valid"], a["n_rows"],
+                                      a["cu"], a["n_resp"], a["adv"], a["count"], a["diag"],
+                                      C.byref(params) if params is not None else None, a["wt"], a["loss"], a["g"])
+
+    assert scale() == -1
+    assert scale(g=None) == -1
+    assert scale(lr=None) == -1
+    assert scale(adv=None) == -1
+    assert scale(params=None) == -1
+    assert scale(n_rows=-3) == -2
+    assert scale(n_resp=0) == -2
+    assert scale(n_resp=(1 << 24) + 1) == -2
+    assert scale(params=B.default_params(C=float("inf"))) == -5
+    assert scale(params=B.default_params(clip_eps=-0.1)) == -5
+    assert scale(n_rows=0, lt=None, lr=None, g=None) == -1       # an empty batch needs no per-row arrays
+
+
+def test_fp8_argument_checks():
+    lib = B._lib()
+
+    def quant(**kw):
+        a = dict(ctx=None, logits=FAKE, dtype=B.AIS_BF16, n_rows=3, vocab=100, stride=104, codes=FAKE, cstride=100,
+                 scale=FAKE)
+        a.update(kw)
+        return lib.ais_fp8_quantize_rows(a["ctx"], a["logits"], a["dtype"], a["n_rows"], a["vocab"], a["stride"],
+                                         a["codes"], a["cstride"], a["scale"])
+
+    assert quant() == -1
+    assert quant(codes=None) == -1
+    assert quant(scale=None) == -1
+    assert quant(cstride=99) == -3
+    assert quant(stride=99) == -3
+    assert quant(dtype=2) == -7
+    assert quant(n_rows=2 ** 31) == -2
+    assert quant(logits=C.c_void_p(0x1003)) == -4
+
+    def dequant(**kw):
+        a = dict(ctx=None, codes=FAKE, cstride=100, scale=FAKE, n_rows=3, vocab=100, out=FAKE, dtype=B.AIS_F32,
+                 ostride=100)
+        a.update(kw)
+        return lib.ais_fp8_dequantize_rows(a["ctx"], a["codes"], a["cstride"], a["scale"], a["n_rows"], a["vocab"],
+                                           a["out"], a["dtype"], a["ostride"])
+
+    assert dequant() == -1
+    assert dequant(codes=None) == -1
+    assert dequant(out=None) == -1
+    assert dequant(cstride=64) == -3
+    assert dequant(ostride=64) == -3
+    assert dequant(out=C.c_void_p(0x1002)) == -4                 # fp32 output on a 2-byte boundary
+    assert dequant(dtype=9) == -7
+    assert dequant(vocab=-5) == -2
+
+    def roll(**kw):
+        a = dict(ctx=None, logits=FAKE, dtype=B.AIS_BF16, n_rows=3, vocab=100, stride=100, tok=FAKE, valid=None,
+                 out=FAKE)
+        a.update(kw)
+        return lib.ais_fp8_rollout_logprob(a["ctx"], a["logits"], a["dtype"], a["n_rows"], a["vocab"], a["stride"],
+                                           a["tok"], a["valid"], a["out"])
+
+    assert roll() == -1
+    assert roll(tok=None) == -1
+    assert roll(out=None) == -1
+    assert roll(stride=10) == -3
+    assert roll(dtype=5) == -7
+    assert roll(n_rows=-1) == -2
+
+
+def test_context_and_utility_argument_checks():
+    lib = B._lib()
+    one, f = C.c_int(0), C.c_float(0.0)
+    assert lib.ais_create(None, 0, None) == -1
+    assert lib.ais_destroy(None) == 0                            # destroying nothing is not an error
+    assert lib.ais_set_stream(None, None) == -1
+    assert lib.ais_last_hip_error(None) == 0
+    assert lib.ais_status(None, C.byref(one), 0) == -1
+    assert lib.ais_profile(None, 1) == -1
+    assert lib.ais_profile_read(None, 0, C.byref(f), C.byref(one)) == -1
+    assert lib.ais_copy(None, FAKE, C.c_void_p(0x2000), 64) == -1       # only the context is missing
+    assert lib.ais_copy(None, FAKE, C.c_void_p(0x2000), 8) == -2        # whole 16-byte vectors only
+    assert lib.ais_copy(None, FAKE, C.c_void_p(0x2000), -16) == -2
+    assert lib.ais_copy(None, None, C.c_void_p(0x2000), 64) == -1
+    assert lib.ais_copy(None, C.c_void_p(0x1008), C.c_void_p(0x2000), 64) == -4
+    assert lib.ais_copy(None, FAKE, C.c_void_p(0x2004), 64) == -4
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_LIB", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
