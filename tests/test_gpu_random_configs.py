@@ -86,7 +86,9 @@ def build_case(seed):
     return batch, p, logp_old, logp_ref, extras
 
 
-SEEDS = list(range(int(os.environ.get("AIS_RANDOM_CASES", "160"))))      # more cases for an occasional long run
+# more cases, or another range of seeds, for an occasional long run
+FIRST = int(os.environ.get("AIS_RANDOM_FIRST", "0"))
+SEEDS = list(range(FIRST, FIRST + int(os.environ.get("AIS_RANDOM_CASES", "160"))))
 
 
 @pytest.mark.parametrize("seed", SEEDS)
