@@ -7,7 +7,8 @@ test_oracle_mutants.py): a pin that no plausible mistake can trip is not a pin.
 None of these checks re-types an oracle formula.  They use closed forms worked
 out by hand from Eq. 12-19, library routines (scipy's logsumexp, torch's float64
 autograd), brute force on tiny vocabularies, finite differences, and the
-invariants the paper states (Prop. 2, Prop. 3, the two end-points alpha = 0 / 1).
+invariants the paper states (Prop. 2, Prop. 3, the two end-points alpha = 0 / 1), and
+exact enumeration of the expectation that the appendix's analysis is about.
 """
 from __future__ import annotations
 
@@ -432,6 +433,48 @@ def pin_endpoints_and_on_policy(O):
     assert np.array_equal(same[0], same[1]) and np.array_equal(same[0], same[2])
     adaptive = O.ais_grpo(z, y, valid, cu, logp, rewards, 2)
     assert adaptive["diag"]["alpha"] == 0.0 and np.array_equal(adaptive["dz"], same[0])
+
+
+def pin_exact_expectation_is_policy_gradient(O):
+    """Appendix, Prop. 1's set-up, by exact enumeration.  One prompt, one position, a group that holds every token of a
+    small vocabulary once.  Weighting response x by pi_roll(x) turns the batch sum into the expectation under the
+    rollout policy, so: with alpha = 1 and C above every ratio the estimate *is* the on-policy gradient
+    grad_z E_{x ~ pi_train}[A(x)] = pi * (A - <pi, A>) (a softmax Jacobian applied to A, coded from that
+    formula); with alpha = 0 it is the same expression under pi_roll's sampling, i.e. sum_x pi_roll(x) A(x) (e_x - pi),
+    whose distance from the first is the mismatch bias b_0; a general alpha interpolates the two."""
+    V = 7
+    rng = np.random.default_rng(77)
+    z_row = rng.normal(0, 1.5, size=V)
+    pi_train = np.exp(z_row - scipy_logsumexp(z_row))
+    z_roll = z_row + rng.normal(0, 0.7, size=V)
+    pi_roll = np.exp(z_roll - scipy_logsumexp(z_roll))
+    rewards = np.array([1.0, 0.0, 0.0, 1.0, 1.0, 0.0, 1.0])
+    A = rewards - rewards.mean()                                    # Eq. 3 over the one group
+    z = np.tile(z_row, (V, 1))                                      # every response sees the same context
+    y = np.arange(V)
+    cu = np.arange(V + 1)
+    valid = np.ones(V, dtype=bool)
+    eye = np.eye(V)
+
+    def expectation(alpha, C):
+        out = O.ais_grpo(z, y, valid, cu, np.log(pi_roll), rewards, V, O.Params(alpha_override=alpha, C=C))
+        # the loss is -(1/B) sum_i (...): undo the sign and the 1/B, weight response x by pi_roll(x)
+        return -(V * pi_roll[:, None] * out["dz"]).sum(axis=0)
+
+    C_big = 2.0 * (pi_train / pi_roll).max()
+    g_true = pi_train * (A - pi_train @ A)
+    g0 = (pi_roll * A) @ (eye - pi_train[None, :])
+    np.testing.assert_allclose(expectation(1.0, C_big), g_true, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(expectation(0.0, C_big), g0, rtol=1e-12, atol=1e-15)
+    assert np.abs(g0 - g_true).max() > 1e-2                         # the bias b_0 is really there
+    np.testing.assert_allclose(expectation(0.4, C_big), 0.6 * g0 + 0.4 * g_true, rtol=1e-12, atol=1e-15)
+    # truncation (Eq. 10) leaves a residual bias b_1: ratios above C are cut, so the estimate moves off g_true
+    C_small = 1.0 + 0.5 * ((pi_train / pi_roll).max() - 1.0)
+    g1 = (pi_roll * np.minimum(pi_train / pi_roll, C_small) * A) @ (eye - pi_train[None, :])
+    np.testing.assert_allclose(expectation(1.0, C_small), g1, rtol=1e-12, atol=1e-15)
+    assert np.abs(g1 - g_true).max() > 1e-4
+    # the score function has mean zero under its own policy: a constant advantage carries no gradient
+    assert np.abs(pi_train @ (eye - pi_train[None, :])).max() < 1e-15
 
 
 def pin_clip_region(O):
