@@ -17,12 +17,12 @@ constexpr int kMaxDevices = 64;        // device indices a context may be create
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-// Per-tile partial sums of the diagnostics reduction (level 1 -> level 2).
+// Per-tile partial results of the diagnostics reduction (level 1 -> level 2).  The spread of w_bar travels as
+// (count, mean, sum of squared deviations from the mean), merged pairwise: a variance never comes out of the
+// difference of two large sums.
 struct DiagPartial {
-  double su;      // sum of (w_bar - 1)
-  double su2;     // sum of (w_bar - 1)^2
-  double sw;      // sum of w_bar
-  double sw2;     // sum of w_bar^2
+  double mean_w;  // mean of w_bar over the tile's valid rows
+  double m2_w;    // sum of (w_bar - mean_w)^2
   double sabs;    // sum of |log pi_train - log pi_roll|
   double sd;      // sum of (log pi_train - log pi_roll)
   double sdp;     // sum of |pi_train - pi_roll|

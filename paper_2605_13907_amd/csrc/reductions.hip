@@ -92,6 +92,55 @@ __device__ __forceinline__ V block_sum(V v, V* lds) {
   return r;
 }
 
+// Count, mean and sum of squared deviations from the mean of a set of values.  Sets are merged pairwise (the
+// update of Chan, Golub and LeVeque): the error of the spread scales with the spread itself, not with the mean, and
+// a set of equal values has spread exactly 0 however it was split.
+struct Moments {
+  double n, mean, m2;
+};
+
+__device__ __forceinline__ Moments merge(const Moments& a, const Moments& b) {
+  if (b.n == 0.0) return a;
+  if (a.n == 0.0) return b;
+  const double n = a.n + b.n, delta = b.mean - a.mean;
+  Moments r;
+  r.n = n;
+  r.mean = a.mean + delta * (b.n / n);
+  r.m2 = a.m2 + b.m2 + delta * delta * (a.n * b.n / n);
+  return r;
+}
+
+__device__ __forceinline__ void push(Moments& m, double x) {
+  m.n += 1.0;
+  const double delta = x - m.mean;
+  m.mean += delta / m.n;
+  m.m2 += delta * (x - m.mean);
+}
+
+// Workgroup-wide merge through LDS (3 * kTileThreads doubles) in a fixed tree order; result valid in thread 0.
+__device__ __forceinline__ Moments block_merge(const Moments& v, double* lds) {
+  const int tid = threadIdx.x;
+  lds[tid] = v.n;
+  lds[kTileThreads + tid] = v.mean;
+  lds[2 * kTileThreads + tid] = v.m2;
+  __syncthreads();
+#pragma unroll
+  for (int s = kTileThreads / 2; s > 0; s >>= 1) {
+    if (tid < s) {
+      const Moments a{lds[tid], lds[kTileThreads + tid], lds[2 * kTileThreads + tid]};
+      const Moments b{lds[tid + s], lds[kTileThreads + tid + s], lds[2 * kTileThreads + tid + s]};
+      const Moments r = merge(a, b);
+      lds[tid] = r.n;
+      lds[kTileThreads + tid] = r.mean;
+      lds[2 * kTileThreads + tid] = r.m2;
+    }
+    __syncthreads();
+  }
+  const Moments r{lds[0], lds[kTileThreads], lds[2 * kTileThreads]};
+  __syncthreads();
+  return r;
+}
+
 // True in exactly one workgroup of the grid: the one that finishes last.  Every workgroup calls this once,
 // after its own results are written; the caller's writes are made visible device-wide before the ticket is
 // taken, and the last workgroup sees all of them.  Level 2 of each reduction runs in that workgroup, which
@@ -117,22 +166,21 @@ __device__ void diag_final(const volatile DiagPartial* partial, const int* __res
                            int group_size, const float* __restrict__ rewards, const ais_params& p,
                            float* __restrict__ adv_out, int* __restrict__ count_out, ais_diag* __restrict__ diag_out,
                            const int* __restrict__ status, double* lds_d, long long* lds_i) {
-  double su = 0, su2 = 0, sw = 0, sw2 = 0, sabs = 0, sd = 0, sdp = 0, sa = 0, sa2 = 0, saw = 0, saw2 = 0;
+  Moments mw{0, 0, 0}, ma{0, 0, 0}, maw{0, 0, 0};     // of w_bar, of A and of A w_bar over the valid rows of the batch
+  double sabs = 0, sd = 0, sdp = 0;
   long long cnt = 0, nclip = 0;
   for (int i = threadIdx.x; i < n_resp; i += kTileThreads) {
     // fold this response's tiles in order
-    double r_su = 0, r_su2 = 0, r_sw = 0, r_sw2 = 0, r_sabs = 0;
-    long long r_cnt = 0, r_nclip = 0;
+    Moments r{0, 0, 0};
+    long long r_cnt = 0;
     for (int t = tile_off[i]; t < tile_off[i + 1]; ++t) {
-      r_su += partial[t].su;
-      r_su2 += partial[t].su2;
-      r_sw += partial[t].sw;
-      r_sw2 += partial[t].sw2;
-      r_sabs += partial[t].sabs;
+      const long long c = partial[t].cnt;
+      r = merge(r, Moments{(double)c, partial[t].mean_w, partial[t].m2_w});
+      sabs += partial[t].sabs;
       sd += partial[t].sd;
       sdp += partial[t].sdp;
-      r_cnt += partial[t].cnt;
-      r_nclip += partial[t].nclip;
+      r_cnt += c;
+      nclip += partial[t].nclip;
     }
     // group-relative advantage (Eq. 3): reward minus the mean over the G responses of the prompt
     const int g0 = (i / group_size) * group_size;
@@ -153,24 +201,19 @@ __device__ void diag_final(const volatile DiagPartial* partial, const int* __res
     adv_out[i] = a32;
     count_out[i] = (int)r_cnt;
     a = (double)a32;                     // the advantage every later step sees is the stored fp32 value
-    // token-level moments of A and A w_bar: A is constant over the response's rows
-    su += r_su; su2 += r_su2; sw += r_sw; sw2 += r_sw2; sabs += r_sabs; cnt += r_cnt; nclip += r_nclip;
-    sa += a * (double)r_cnt;
-    sa2 += a * a * (double)r_cnt;
-    saw += a * r_sw;
-    saw2 += a * a * r_sw2;
+    // token-level moments of A and A w_bar: A is constant over the response's rows, so the response's rows
+    // have mean A mean(w_bar) and squared deviations A^2 m2(w_bar)
+    cnt += r_cnt;
+    mw = merge(mw, r);
+    ma = merge(ma, Moments{r.n, a, 0.0});
+    maw = merge(maw, Moments{r.n, a * r.mean, a * a * r.m2});
   }
-  su = block_sum(su, lds_d);
-  su2 = block_sum(su2, lds_d);
-  sw = block_sum(sw, lds_d);
-  sw2 = block_sum(sw2, lds_d);
+  mw = block_merge(mw, lds_d);
+  ma = block_merge(ma, lds_d);
+  maw = block_merge(maw, lds_d);
   sabs = block_sum(sabs, lds_d);
   sd = block_sum(sd, lds_d);
   sdp = block_sum(sdp, lds_d);
-  sa = block_sum(sa, lds_d);
-  sa2 = block_sum(sa2, lds_d);
-  saw = block_sum(saw, lds_d);
-  saw2 = block_sum(saw2, lds_d);
   cnt = block_sum(cnt, lds_i);
   nclip = block_sum(nclip, lds_i);
   if (threadIdx.x != 0) return;
@@ -185,17 +228,8 @@ __device__ void diag_final(const volatile DiagPartial* partial, const int* __res
     d.alpha = 0.0; d.kl_roll_train = 0.0; d.mean_abs_dp = 0.0;
   } else {
     const double N = (double)cnt;
-    // Two sets of moments: of u = w_bar - 1, which do not cancel when the weights sit near 1 (the usual case), and
-    // of w_bar itself, which keep the mean and the spread when the weights are far below 1 (a trainer that has
-    // drifted by hundreds of nats: 1 + mean(u) would round to 0 there).  Variance is shift-invariant.
-    const double mu_u = su / N;
-    if (1.0 + mu_u >= 0.5) {
-      d.mean_w = 1.0 + mu_u;
-      d.var_w = fmax(0.0, su2 / N - mu_u * mu_u);
-    } else {
-      d.mean_w = sw / N;
-      d.var_w = fmax(0.0, sw2 / N - d.mean_w * d.mean_w);
-    }
+    d.mean_w = mw.mean;
+    d.var_w = mw.m2 / N;
     // every truncated ratio underflowed to 0: CV^2 is 0 / 0; read as 0 (equal weights), like the empty batch
     const double cv = d.mean_w > 0.0 ? sqrt(d.var_w) / d.mean_w : 0.0;    // std / mean: mean^2 alone may underflow
     d.cv2 = cv * cv;
@@ -203,9 +237,8 @@ __device__ void diag_final(const volatile DiagPartial* partial, const int* __res
     d.alpha_ess = 1.0 / sqrt(1.0 + d.cv2);                    // Eq. 12
     d.dbar = sabs / N;                                        // Eq. 13
     d.alpha_mis = fmin(1.0, d.dbar / (double)p.delta);        // Eq. 14
-    const double ma = sa / N, maw = saw / N;
-    d.std_a = sqrt(fmax(0.0, sa2 / N - ma * ma));
-    d.std_aw = sqrt(fmax(0.0, saw2 / N - maw * maw));
+    d.std_a = sqrt(ma.m2 / N);
+    d.std_aw = sqrt(maw.m2 / N);
     // Eq. 15; with eps_std = 0 and all advantages equal the ratio is 0 / 0: nothing to amplify, read as 0
     const double den = d.std_a + (double)p.eps_std;
     d.dsigma = den > 0.0 ? d.std_aw / den : 0.0;
@@ -227,7 +260,7 @@ __global__ __launch_bounds__(kTileThreads) void diag_reduce_kernel(
     const int* __restrict__ tile_off, DiagPartial* partial, int group_size, const float* __restrict__ rewards,
     ais_params p, float* __restrict__ adv_out, int* __restrict__ count_out, ais_diag* __restrict__ diag_out,
     const int* __restrict__ status, int* ticket) {
-  __shared__ double lds_d[kTileThreads];
+  __shared__ double lds_d[3 * kTileThreads];
   __shared__ long long lds_i[kTileThreads];
   const int b = blockIdx.x;
   if (b < tile_off[n_resp]) {                        // uniform for the workgroup; the others only take a ticket
@@ -237,18 +270,15 @@ __global__ __launch_bounds__(kTileThreads) void diag_reduce_kernel(
     const long long r0 = lo + (long long)(b - tile_off[i]) * kTileRows;
     const long long r1 = min(hi, r0 + kTileRows);
     const double lnC = log((double)p.C);
-    double su = 0, su2 = 0, sw = 0, sw2 = 0, sabs = 0, sd = 0, sdp = 0;
+    Moments mw{0, 0, 0};
+    double sabs = 0, sd = 0, sdp = 0;
     long long cnt = 0, nclip = 0;
     for (long long n = r0 + threadIdx.x; n < r1; n += kTileThreads) {
       if (valid != nullptr && valid[n] == 0) continue;
       const double lt = (double)logp_train[n], lr = (double)logp_roll[n];
       const double d = lt - lr;                                            // log rho (Alg. 1, sampler-trainer ratio)
       const double w = exp(fmin(d, lnC));                                  // w_bar = min(rho, C) (Eq. 10)
-      const double u = w - 1.0;
-      su += u;
-      su2 += u * u;
-      sw += w;
-      sw2 += w * w;
+      push(mw, w);
       sabs += fabs(d);
       sd += d;
       sdp += fabs(exp(lt) - exp(lr));
@@ -256,10 +286,9 @@ __global__ __launch_bounds__(kTileThreads) void diag_reduce_kernel(
       nclip += (d > lnC) ? 1 : 0;
     }
     DiagPartial t;
-    t.su = block_sum(su, lds_d);
-    t.su2 = block_sum(su2, lds_d);
-    t.sw = block_sum(sw, lds_d);
-    t.sw2 = block_sum(sw2, lds_d);
+    mw = block_merge(mw, lds_d);
+    t.mean_w = mw.mean;
+    t.m2_w = mw.m2;
     t.sabs = block_sum(sabs, lds_d);
     t.sd = block_sum(sd, lds_d);
     t.sdp = block_sum(sdp, lds_d);

@@ -81,3 +81,45 @@ def test_scalars_at_scale(name, stale):
     np.testing.assert_allclose(P.to_np64(g), g_ref * op.inv_temperature, rtol=2e-6, atol=1e-30)
     scale = float(np.sum(np.abs(adv_ref)) / n_resp) + op.beta_kl
     assert abs(float(loss.item()) - loss_ref) <= 1e-6 * max(abs(loss_ref), scale, 1e-12), (float(loss.item()), loss_ref)
+
+
+@pytest.mark.parametrize("shift", [-40.0, -0.3125, 0.0, 0.078125, 9.0])     # dyadic: the sum below is exact
+@pytest.mark.parametrize("n_resp,length", [(2, 3), (8, 700), (64, 5_000)])
+def test_equal_weights_have_no_spread(shift, n_resp, length):
+    """Every valid row has the same ratio (all truncated at C for shift = 9, all exp(shift) otherwise) and the valid
+    rows sit in responses of equal advantage: the spread statistics are those of a constant.  The variance of equal
+    numbers is 0 whatever the way the rows were cut into tiles, and the advantage-weighted spread of Eq. 15 is
+    0 / (0 + eps): rounding noise divided by the 1e-6 stabiliser would show up here as a spurious amplification."""
+    rng = np.random.default_rng(n_resp * 1000 + length)
+    cu = (np.arange(n_resp + 1) * length).astype(np.int64)
+    R = int(cu[-1])
+    logp_roll = -np.abs(rng.normal(2.0, 1.0, size=R)).astype(np.float32)
+    logp_roll = np.round(logp_roll * 64) / 64 - 50.0                  # multiples of 1/64: adding `shift` is exact in fp32
+    logp_train = (logp_roll + np.float32(shift)).astype(np.float32)
+    assert np.all(logp_train.astype(np.float64) - logp_roll.astype(np.float64) == float(np.float32(shift)))
+    rewards = np.tile(np.array([1.0, 0.0], dtype=np.float32), n_resp // 2)
+    valid = np.zeros(R, dtype=np.uint8)
+    for i in range(0, n_resp, 2):                                     # only the rewarded responses are evaluated
+        valid[cu[i]:cu[i + 1]] = rng.random(length) < 0.7
+    valid[0] = 1
+    p = B.default_params()
+    op = P.oracle_params(p)
+    adv_ref = O.group_advantages(rewards.astype(np.float64), 2, op.adv_mode, op.eps_std)
+    rd = O.diagnostics(logp_train, logp_roll.astype(np.float32), valid, cu, adv_ref, op)
+    ctx = B.AisContext()
+    t = lambda a: torch.from_numpy(a).cuda()
+    adv, count, diag = ctx.diagnostics(t(logp_train), t(logp_roll.astype(np.float32)), t(valid), t(cu), t(rewards), 2, p)
+    torch.cuda.synchronize()
+    d = ctx.read_diag(diag)
+    assert ctx.status() == 0
+    ctx.close()
+    w = min(np.exp(float(np.float32(shift))), 5.0)
+    print(f"shift {shift}: w_bar {w:.4g}, gpu var_w {d['var_w']:.3e} std_aw {d['std_aw']:.3e} dsigma {d['dsigma']:.3e}; "
+          f"oracle {rd['var_w']:.3e} {rd['std_aw']:.3e} {rd['dsigma']:.3e}", flush=True)
+    assert d["n_valid"] == rd["n_valid"] == int(valid.sum())
+    P.rel_close(d["mean_w"], w, rel=1e-12, what="mean_w")
+    assert d["var_w"] == 0.0 and d["cv2"] == 0.0 and d["alpha_ess"] == 1.0
+    assert d["std_a"] == 0.0 and d["std_aw"] == 0.0 and d["dsigma"] == 0.0 and d["alpha_var"] == 0.0
+    # the oracle's two-pass forms agree up to the rounding of its own mean
+    assert rd["var_w"] <= 1e-28 * w * w and rd["std_aw"] <= 1e-14 * w and rd["dsigma"] <= 1e-8 * w
+    P.rel_close(d["alpha"], rd["alpha"], rel=1e-9, floor=1e-12, what="alpha")
