@@ -3,6 +3,8 @@ the paper's defaults, and rejects bad arguments on the host before touching any 
 import ctypes as C
 import os
 import re
+import subprocess
+import sys
 
 import pytest
 
@@ -283,3 +285,10 @@ def test_header_is_plain_c_and_links(tmp_path):
                     src, "-o", str(exe), B.LIB_PATH, f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib"], check=True)
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True)
     assert out.stdout.strip() == "0"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=300)
+    assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
+    assert not r.stdout.strip().startswith("{")              # no result line for a run that did not happen
