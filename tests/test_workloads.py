@@ -148,3 +148,34 @@ def test_readout_generator_structure_and_determinism():
     # a slice of the rows is the leading part of the same batch structure
     c = W.generate_readout(shape, n_rows=100)
     assert c.hidden.shape[0] == 100 and torch.equal(c.valid, valid[:100])
+
+
+def test_oracle_pool_equals_the_oracle_in_one_process():
+    """The worker pool of the CPU-baseline timing only moves data: its results are those of the plain oracle."""
+    import numpy as np
+    import oracle.ais_oracle as O
+    from oracle.pool import OraclePool, widen
+
+    rng = np.random.default_rng(5)
+    R, V, G = 96, 300, 4
+    z32 = rng.normal(0, 3, size=(R, V)).astype(np.float32)
+    bits = (z32.view(np.uint32) >> 16).astype(np.uint16)             # bf16 bit patterns (truncated fp32)
+    z = widen(bits, "bf16")
+    assert np.array_equal(z, ((bits.astype(np.uint32) << 16).view(np.float32)).astype(np.float64))
+    y = rng.integers(0, V, size=R)
+    valid = (rng.random(R) < 0.8).astype(np.uint8)
+    cu = np.arange(G + 1, dtype=np.int64) * (R // G)
+    lp_roll = rng.normal(-3, 0.5, size=R)
+    rewards = np.array([1.0, 0.0, 0.0, 1.0])
+    ref = O.ais_grpo(z, y, valid, cu, lp_roll, rewards, G, O.Params())
+    pool = OraclePool(2)
+    try:
+        path = pool.share(bits)
+        out = pool.whole_path(path, R, "bf16", y, valid, cu, lp_roll, rewards, G, O.Params(), row_chunk=20)
+    finally:
+        pool.close()
+    import os
+    assert not os.path.exists(path)                                  # the shared file is gone after close()
+    assert np.array_equal(out["logp"], ref["logp"]) and np.array_equal(out["lse"], ref["lse"])
+    assert out["loss"] == ref["loss"] and np.array_equal(out["g"], ref["g"])
+    assert abs(out["abs_sum"] - np.abs(ref["dz"]).sum()) <= 1e-12 * np.abs(ref["dz"]).sum()
