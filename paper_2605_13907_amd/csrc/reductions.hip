@@ -76,18 +76,27 @@ __device__ __forceinline__ int find_response(const int* __restrict__ tile_off, i
   return lo;
 }
 
-// Workgroup-wide sum through LDS in a fixed tree order; result valid in thread 0.
+constexpr int kWaves = kTileThreads / 64;
+
+// Sum over a wavefront by lane shuffles, in a fixed tree order; lane 0 holds the result.  No barrier is involved:
+// these kernels are latency-bound and a workgroup barrier per tree level was most of their time.
+template <typename V>
+__device__ __forceinline__ V wave_sum(V v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off);
+  return v;
+}
+
+// Workgroup-wide sum: wavefront sums, then the kWaves partials through LDS in index order.  `lds` holds kWaves
+// values; the result is valid in every thread.  Must be called by all threads of the workgroup.
 template <typename V>
 __device__ __forceinline__ V block_sum(V v, V* lds) {
-  const int tid = threadIdx.x;
-  lds[tid] = v;
+  v = wave_sum(v);
+  if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
   __syncthreads();
-#pragma unroll
-  for (int s = kTileThreads / 2; s > 0; s >>= 1) {
-    if (tid < s) lds[tid] += lds[tid + s];
-    __syncthreads();
-  }
   V r = lds[0];
+#pragma unroll
+  for (int w = 1; w < kWaves; ++w) r += lds[w];
   __syncthreads();
   return r;
 }
@@ -117,28 +126,65 @@ __device__ __forceinline__ void push(Moments& m, double x) {
   m.m2 += delta * (x - m.mean);
 }
 
-// Workgroup-wide merge through LDS (3 * kTileThreads doubles) in a fixed tree order; result valid in thread 0.
-__device__ __forceinline__ Moments block_merge(const Moments& v, double* lds) {
-  const int tid = threadIdx.x;
-  lds[tid] = v.n;
-  lds[kTileThreads + tid] = v.mean;
-  lds[2 * kTileThreads + tid] = v.m2;
+__device__ __forceinline__ Moments wave_merge(Moments m) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const Moments o{__shfl_down(m.n, off), __shfl_down(m.mean, off), __shfl_down(m.m2, off)};
+    m = merge(m, o);       // lanes whose partner is beyond the wavefront merge rubbish; lane 0 never depends on them
+  }
+  return m;
+}
+
+// One workgroup-wide reduction of everything a level of the diagnostics needs, with a single barrier pair: NM sets
+// of moments, ND plain sums and NI integer sums.  `lds_d` holds (3 NM + ND) kWaves doubles, `lds_i` NI kWaves
+// integers.  Results replace the arguments and are valid in every thread.  Must be called by all threads.
+template <int NM, int ND, int NI>
+__device__ __forceinline__ void block_reduce(Moments (&m)[NM], double (&d)[ND], long long (&c)[NI], double* lds_d,
+                                             long long* lds_i) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+  for (int k = 0; k < NM; ++k) m[k] = wave_merge(m[k]);
+#pragma unroll
+  for (int k = 0; k < ND; ++k) d[k] = wave_sum(d[k]);
+#pragma unroll
+  for (int k = 0; k < NI; ++k) c[k] = wave_sum(c[k]);
+  if (lane == 0) {
+#pragma unroll
+    for (int k = 0; k < NM; ++k) {
+      lds_d[(3 * k + 0) * kWaves + w] = m[k].n;
+      lds_d[(3 * k + 1) * kWaves + w] = m[k].mean;
+      lds_d[(3 * k + 2) * kWaves + w] = m[k].m2;
+    }
+#pragma unroll
+    for (int k = 0; k < ND; ++k) lds_d[(3 * NM + k) * kWaves + w] = d[k];
+#pragma unroll
+    for (int k = 0; k < NI; ++k) lds_i[k * kWaves + w] = c[k];
+  }
   __syncthreads();
 #pragma unroll
-  for (int s = kTileThreads / 2; s > 0; s >>= 1) {
-    if (tid < s) {
-      const Moments a{lds[tid], lds[kTileThreads + tid], lds[2 * kTileThreads + tid]};
-      const Moments b{lds[tid + s], lds[kTileThreads + tid + s], lds[2 * kTileThreads + tid + s]};
-      const Moments r = merge(a, b);
-      lds[tid] = r.n;
-      lds[kTileThreads + tid] = r.mean;
-      lds[2 * kTileThreads + tid] = r.m2;
-    }
-    __syncthreads();
+  for (int k = 0; k < NM; ++k) {
+    Moments r{lds_d[(3 * k + 0) * kWaves], lds_d[(3 * k + 1) * kWaves], lds_d[(3 * k + 2) * kWaves]};
+#pragma unroll
+    for (int v = 1; v < kWaves; ++v)
+      r = merge(r, Moments{lds_d[(3 * k + 0) * kWaves + v], lds_d[(3 * k + 1) * kWaves + v],
+                           lds_d[(3 * k + 2) * kWaves + v]});
+    m[k] = r;
   }
-  const Moments r{lds[0], lds[kTileThreads], lds[2 * kTileThreads]};
+#pragma unroll
+  for (int k = 0; k < ND; ++k) {
+    double r = lds_d[(3 * NM + k) * kWaves];
+#pragma unroll
+    for (int v = 1; v < kWaves; ++v) r += lds_d[(3 * NM + k) * kWaves + v];
+    d[k] = r;
+  }
+#pragma unroll
+  for (int k = 0; k < NI; ++k) {
+    long long r = lds_i[k * kWaves];
+#pragma unroll
+    for (int v = 1; v < kWaves; ++v) r += lds_i[k * kWaves + v];
+    c[k] = r;
+  }
   __syncthreads();
-  return r;
 }
 
 // True in exactly one workgroup of the grid: the one that finishes last.  Every workgroup calls this once,
@@ -208,14 +254,15 @@ __device__ void diag_final(const volatile DiagPartial* partial, const int* __res
     ma = merge(ma, Moments{r.n, a, 0.0});
     maw = merge(maw, Moments{r.n, a * r.mean, a * a * r.m2});
   }
-  mw = block_merge(mw, lds_d);
-  ma = block_merge(ma, lds_d);
-  maw = block_merge(maw, lds_d);
-  sabs = block_sum(sabs, lds_d);
-  sd = block_sum(sd, lds_d);
-  sdp = block_sum(sdp, lds_d);
-  cnt = block_sum(cnt, lds_i);
-  nclip = block_sum(nclip, lds_i);
+  {
+    Moments m[3] = {mw, ma, maw};
+    double d[3] = {sabs, sd, sdp};
+    long long c[2] = {cnt, nclip};
+    block_reduce(m, d, c, lds_d, lds_i);
+    mw = m[0]; ma = m[1]; maw = m[2];
+    sabs = d[0]; sd = d[1]; sdp = d[2];
+    cnt = c[0]; nclip = c[1];
+  }
   if (threadIdx.x != 0) return;
 
   ais_diag d;
@@ -260,8 +307,8 @@ __global__ __launch_bounds__(kTileThreads) void diag_reduce_kernel(
     const int* __restrict__ tile_off, DiagPartial* partial, int group_size, const float* __restrict__ rewards,
     ais_params p, float* __restrict__ adv_out, int* __restrict__ count_out, ais_diag* __restrict__ diag_out,
     const int* __restrict__ status, int* ticket) {
-  __shared__ double lds_d[3 * kTileThreads];
-  __shared__ long long lds_i[kTileThreads];
+  __shared__ double lds_d[12 * kWaves];          // three sets of moments and three sums per wavefront
+  __shared__ long long lds_i[2 * kWaves];
   const int b = blockIdx.x;
   if (b < tile_off[n_resp]) {                        // uniform for the workgroup; the others only take a ticket
     const int i = find_response(tile_off, n_resp, b);
@@ -285,15 +332,18 @@ __global__ __launch_bounds__(kTileThreads) void diag_reduce_kernel(
       cnt += 1;
       nclip += (d > lnC) ? 1 : 0;
     }
+    Moments m[1] = {mw};
+    double d[3] = {sabs, sd, sdp};
+    long long c[2] = {cnt, nclip};
+    block_reduce(m, d, c, lds_d, lds_i);
     DiagPartial t;
-    mw = block_merge(mw, lds_d);
-    t.mean_w = mw.mean;
-    t.m2_w = mw.m2;
-    t.sabs = block_sum(sabs, lds_d);
-    t.sd = block_sum(sd, lds_d);
-    t.sdp = block_sum(sdp, lds_d);
-    t.cnt = block_sum(cnt, lds_i);
-    t.nclip = block_sum(nclip, lds_i);
+    t.mean_w = m[0].mean;
+    t.m2_w = m[0].m2;
+    t.sabs = d[0];
+    t.sd = d[1];
+    t.sdp = d[2];
+    t.cnt = c[0];
+    t.nclip = c[1];
     if (threadIdx.x == 0) partial[b] = t;
   }
   // ---- level 2, in the workgroup that finishes last ----
@@ -316,7 +366,7 @@ __global__ __launch_bounds__(kTileThreads) void row_coeff_kernel(
     const int* __restrict__ count, const ais_diag* __restrict__ diag, ais_params p,
     const int* __restrict__ tile_off, double* partial, float* __restrict__ g_out,
     float* __restrict__ wtilde_out, float g_scale, double* __restrict__ loss_out, int* ticket) {
-  __shared__ double lds_d[kTileThreads];
+  __shared__ double lds_d[kWaves];
   const int b = blockIdx.x;
   if (b < tile_off[n_resp]) {                        // uniform for the workgroup; the others only take a ticket
     const int i = find_response(tile_off, n_resp, b);
