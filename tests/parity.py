@@ -122,8 +122,13 @@ def compare_scalars(ctx, out, ref, batch):
         t_cv2 = (t_var + 2.0 * var_w * Ew / max(mean_w, 1e-300)) / max(mean_w * mean_w, 1e-300) if mean_w > 0 else 0.0
         den = rd["std_a"] + op.eps_std
         t_dsig = 2.0 * a_max * Ew / den if den > 0 else 0.0
+        # a ratio within E of the truncation level may fall on either side of it: each such token moves the
+        # truncated share by 1 / N
+        d_ref = ref["logp"] - to_np64(batch.logp_roll)
+        on_edge = int(np.sum(valid & (np.abs(d_ref - np.log(op.C)) <= 2.0 * E + 1e-12)))
         extra = dict(mean_w=Ew, var_w=t_var, cv2=t_cv2, ess_ratio=t_cv2, alpha_ess=t_cv2, dbar=E, std_a=0.0,
-                     std_aw=2.0 * a_max * Ew, dsigma=t_dsig, alpha_mis=E / op.delta, clip_frac=0.0, mean_abs_dp=E)
+                     std_aw=2.0 * a_max * Ew, dsigma=t_dsig, alpha_mis=E / op.delta,
+                     clip_frac=on_edge / rd["n_valid"], mean_abs_dp=E)
         # weights below 1e-140 have squares at the bottom of the fp64 range: the oracle's own variance is made of
         # denormals there and says nothing; only finiteness and range are checked for the spread statistics
         skip = ("var_w", "cv2", "ess_ratio", "alpha_ess") if 0.0 < mean_w < 1e-140 else ()
