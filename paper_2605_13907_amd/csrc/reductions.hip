@@ -2,11 +2,13 @@
 //
 // The batch is a set of variable-length segments (responses) of rows, some rows masked out.  A small
 // plan kernel cuts every response into tiles of kTileRows rows; level 1 reduces one tile per workgroup
-// through LDS to a partial; level 2, run by whichever workgroup of the same launch finishes last, folds the
-// partials of each response in order, forms the group-relative advantages (Eq. 3) and the batch moments, and evaluates the three diagnostics and
-// the mixing coefficient (Eq. 12-17).  Everything is accumulated in fp64 in a fixed order (no floating
-// point atomics), so results are bit-reproducible from run to run.  These kernels move a few bytes per
-// row (about a megabyte per batch) and are latency-bound; the time of the path is in the two sweeps.
+// (lane shuffles, then one exchange through LDS) to a partial; level 2, run by whichever workgroup of the
+// same launch finishes last, folds the partials of each response in order, forms the group-relative
+// advantages (Eq. 3) and the batch moments, and evaluates the three diagnostics and the mixing coefficient
+// (Eq. 12-17).  Everything is accumulated in fp64 in a fixed order (no floating point atomics), so results
+// are bit-reproducible from run to run; spreads are carried as pairwise-merged (count, mean, squared
+// deviations) triples, never as differences of power sums.  These kernels move a few bytes per row (about a
+// megabyte per batch) and are latency-bound; the time of the path is in the two sweeps.
 #include "ais_internal.h"
 
 namespace ais {
