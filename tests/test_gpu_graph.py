@@ -81,3 +81,45 @@ def test_lm_head_graph_replays_match_eager():
         assert torch.equal(got[0], ref[0]) and torch.equal(got[1], ref[1]), f"replay {it} differs from the eager result"
     assert ctx.status() == 0
     ctx.close()
+
+
+def test_one_sweep_and_fp8_graph_replays_match_eager():
+    """The one-sweep path and the three FP8 kernels under capture, at two row-width classes, replayed on new
+    inputs."""
+    ctx = B.AisContext()
+    p = B.default_params(inv_temperature=1.0 / 0.9)
+    for vocab in (21_512, 4104):
+        shape = W.config(2).scaled(vocab=vocab, len_div=64, seed=29)
+        batch = W.generate(shape, "cuda")
+        logits0 = batch.logits.clone()
+
+        def step():
+            out = ctx.step_one_sweep(batch, p)
+            codes, scale = ctx.fp8_quantize_rows(batch.logits)
+            zr = ctx.fp8_dequantize_rows(codes, scale, dtype=batch.logits.dtype)
+            lpr = ctx.fp8_rollout_logprob(batch.logits, batch.token_ids, batch.valid)
+            return [out[k] for k in ("logp", "lse", "diag", "loss", "wtilde", "sgrad", "g")] + [codes, scale, zr, lpr]
+
+        names = ("logp", "lse", "diag", "loss", "wtilde", "sgrad", "g", "codes", "scale", "dequantised", "logp_roll")
+        step()                                 # warm-up: sizes the context's workspace outside the capture
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                held = step()
+        torch.cuda.synchronize()
+        for it in range(3):
+            batch.logits.copy_(logits0 * (1.0 - 0.07 * it))
+            batch.logp_roll.sub_(0.02 * it * batch.valid.float())
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            got = [t.clone() for t in held]
+            ref = step()
+            torch.cuda.synchronize()
+            for a, b, name in zip(got, ref, names):
+                assert torch.equal(a, b), f"vocab {vocab}, replay {it}: {name} differs from the eager result"
+        del graph, held
+    assert ctx.status() == 0
+    ctx.close()
