@@ -172,8 +172,10 @@ int ais_diagnostics(ais_ctx* ctx, const float* logp_train, const float* logp_rol
                     float* adv_out, int* count_out, ais_diag* diag_out);
 
 /* Loss and gradient (Alg. 1, "Advantage Rectification" and "Policy Update"; Eq. 18, 19).
- * With w_bar = min(exp(logp_train - logp_roll), C), w_tilde = 1 + alpha (w_bar - 1) and
- * rho_on = exp(logp_train - logp_old) (1 if logp_old is NULL):
+ * The two ratios of Sec. 3.2 are kept apart: the sampler-trainer ratio is taken at the checkpoint theta_old that
+ * generated the rollout, the old-new ratio between theta_old and the current parameters.  With
+ * l_old = logp_old (logp_train if logp_old is NULL), w_bar = min(exp(l_old - logp_roll), C),
+ * w_tilde = 1 + alpha (w_bar - 1) and rho_on = exp(logp_train - l_old) (1 if logp_old is NULL):
  *   loss = -(1/n_resp) sum_i (1/|o_i|) sum_{valid t in i}
  *              [ w_tilde min(rho_on A_i, clip(rho_on, 1 -+ clip_eps) A_i) - beta_kl k3_t ]
  *   dlogits[n, v] = g_n * inv_temperature * (softmax(inv_temperature z_n)_v - 1[v = y_n])
@@ -181,8 +183,13 @@ int ais_diagnostics(ais_ctx* ctx, const float* logp_train, const float* logp_rol
  * clipped branch is the minimum), alpha / w_tilde / A being constants, and
  * k3 = exp(q) - q - 1, q = logp_ref - logp_train (used only if logp_ref != NULL and beta_kl > 0).
  *   logits, token_ids, valid, cu_rows   as above (the same arrays given to the first two calls)
- *   logp_train, lse   outputs of ais_token_logprob;  adv, count, diag  outputs of ais_diagnostics
+ *   logp_train, lse   outputs of ais_token_logprob on the current logits;  adv, count, diag  outputs of
+ *               ais_diagnostics (which, when logp_old is given, was fed logp_old as its logp_train: the
+ *               diagnostics of Alg. 1 are taken at theta_old)
  *   logp_old, logp_ref   [n_rows] fp32 or NULL
+ *   cu_rows     when this is the array (same pointer, sizes and stream) that the last ais_diagnostics call on the
+ *               context was given, the row tiling that call left in the workspace is reused: the array must still
+ *               hold the same values, and a HIP graph should capture the calls of a step together
  *   wtilde_out  [n_rows] fp32 (0 where valid == 0); may be NULL
  *   loss_out    one double in device memory
  *   dlogits     [n_rows, row_stride] of `dtype`, same pitch as logits; every element of the

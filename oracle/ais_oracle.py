@@ -26,6 +26,10 @@ Readings where the paper is silent:
   * |o_i| is the number of evaluated positions of response i; a response with none contributes 0.
   * the 1/G sum and the expectation over prompts become 1/B with B = all responses passed.
   * log pi_old absent  =>  rho_on = 1 (first update after the rollout, theta = theta_old).
+  * log pi_old given (theta has moved on from theta_old): the sampler-trainer ratio, the diagnostics and
+    alpha are taken at theta_old, as Alg. 1 writes them, so w_bar = min(exp(log pi_old - log pi_roll), C)
+    does not move during optimisation; only rho_on = exp(log pi_theta - log pi_old) does (Sec. 3.2: the two
+    ratios are orthogonal).
   * the KL term of Eq. 19 names no estimator; the optional term here is the per-token
     k3 form exp(q) - q - 1 with q = log pi_ref - log pi_theta, averaged like the surrogate.
     Parity unpinned by the paper for that term (pinned here only by its own closed forms).
@@ -218,14 +222,17 @@ def row_terms(logp, logp_old, logp_ref, wtilde, a, p: Params):
 
 def loss_and_row_coeff(logp, logp_roll, logp_old, logp_ref, valid, cu_rows, adv, count, alpha, p: Params):
     """loss = -(1/B) sum_i (1/|o_i|) sum_{t valid} [ w_tilde s - beta_kl k3 ]  (Eq. 19, negated),
-    w_tilde [R] and g [R] with  d loss / d z[n, v] = g_n (softmax(z_n)_v - 1[v = y_n]) * inv_temperature."""
+    w_tilde [R] and g [R] with  d loss / d z[n, v] = g_n (softmax(z_n)_v - 1[v = y_n]) * inv_temperature.
+    The rectification weight comes from the sampler-trainer ratio at the checkpoint that generated the
+    rollout (Alg. 1, "Sampler-Trainer ratio"): log pi_old where it is given, the current log-probs otherwise."""
     logp = _f64(logp)
     R = logp.size
     valid = np.ones(R, dtype=bool) if valid is None else np.asarray(valid).astype(bool)
     cu = np.asarray(cu_rows).astype(np.int64)
     B = cu.size - 1
     seq = rows_to_responses(cu, R)
-    _, _, wbar = importance_weights(logp, logp_roll, p.C)
+    logp_at_rollout = logp if logp_old is None else _f64(logp_old)
+    _, _, wbar = importance_weights(logp_at_rollout, logp_roll, p.C)
     wtilde = mixed_weights(wbar, alpha, valid)
     a = _f64(adv)[seq]
     obj, dobj, _, _ = row_terms(logp, logp_old, logp_ref, wtilde, a, p)
@@ -263,7 +270,8 @@ def ais_grpo(z, y, valid, cu_rows, logp_roll, rewards, group_size: int, p: Optio
     p = p or Params()
     logp, lse = token_logprob(z, y, valid, p.inv_temperature)
     adv = group_advantages(rewards, group_size, p.adv_mode, p.eps_std)
-    diag = diagnostics(logp, logp_roll, valid, cu_rows, adv, p)
+    # "Adaptive Coefficient Estimation" of Alg. 1 works on log pi_train(. | theta_old)
+    diag = diagnostics(logp if logp_old is None else logp_old, logp_roll, valid, cu_rows, adv, p)
     loss, wtilde, g = loss_and_row_coeff(logp, logp_roll, logp_old, logp_ref, valid, cu_rows, adv,
                                          diag["count"], diag["alpha"], p)
     out = dict(logp=logp, lse=lse, adv=adv, diag=diag, loss=loss, wtilde=wtilde, g=g)

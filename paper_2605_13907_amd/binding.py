@@ -128,9 +128,23 @@ def _ptr(t: Optional[torch.Tensor], dtype=None, numel=None, name="tensor", devic
     return C.c_void_p(t.data_ptr())
 
 
-def _logits_geometry(logits: torch.Tensor):
+def _dev_ptr(t: torch.Tensor, device: torch.device, name: str):
+    """Device pointer of a buffer whose layout the caller has already checked: it must live on the context's GPU
+    (a host or foreign pointer handed to a kernel is a GPU memory fault, not an error code)."""
+    if not isinstance(t, torch.Tensor):
+        raise TypeError(f"{name} must be a torch.Tensor")
+    if not t.is_cuda or t.device != device:
+        raise ValueError(f"{name} is on {t.device}, expected {device}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _logits_geometry(logits: torch.Tensor, device: Optional[torch.device] = None, name: str = "logits"):
+    if not isinstance(logits, torch.Tensor):
+        raise TypeError(f"{name} must be a torch.Tensor")
     if logits.dim() != 2 or logits.stride(1) != 1 and logits.shape[1] > 1:
-        raise ValueError("logits must be [n_rows, vocab] with unit stride along the vocabulary")
+        raise ValueError(f"{name} must be [n_rows, vocab] with unit stride along the vocabulary")
+    if device is not None and (not logits.is_cuda or logits.device != device):
+        raise ValueError(f"{name} is on {logits.device}, expected {device}")
     n_rows, vocab = logits.shape
     row_stride = logits.stride(0) if n_rows > 1 else max(vocab, logits.stride(0))
     return n_rows, vocab, row_stride
@@ -174,8 +188,8 @@ class AisContext:
     # ------------------------------------------------------------------ the three calls
     def token_logprob(self, logits, token_ids, valid=None, inv_temperature: float = 1.0):
         """-> (logp [R] fp32, lse [R] fp32).  See ais_token_logprob in include/ais.h."""
-        n_rows, vocab, row_stride = _logits_geometry(logits)
         dev = self.device
+        n_rows, vocab, row_stride = _logits_geometry(logits, dev)
         logp = torch.empty(n_rows, dtype=torch.float32, device=dev)
         lse = torch.empty(n_rows, dtype=torch.float32, device=dev)
         self._sync_stream()
@@ -214,12 +228,13 @@ class AisContext:
         Pass dlogits=logits to overwrite the logits in place."""
         p = params or default_params()
         dev = self.device
-        n_rows, vocab, row_stride = _logits_geometry(logits)
+        n_rows, vocab, row_stride = _logits_geometry(logits, dev)
         n_resp = adv.numel()
         if dlogits is None:
             dlogits = torch.empty_strided(logits.shape, logits.stride(), dtype=logits.dtype, device=dev)
         elif dlogits.dtype != logits.dtype or dlogits.shape != logits.shape or dlogits.stride() != logits.stride():
             raise ValueError("dlogits must have the dtype, shape and strides of logits")
+        _dev_ptr(dlogits, dev, "dlogits")
         wtilde = torch.empty(n_rows, dtype=torch.float32, device=dev) if want_wtilde else None
         loss = torch.empty(1, dtype=torch.float64, device=dev)
         self._sync_stream()
@@ -242,8 +257,9 @@ class AisContext:
         """The whole path on one workloads.RolloutBatch: the three calls back to back on one stream."""
         p = params or default_params()
         logp, lse = self.token_logprob(batch.logits, batch.token_ids, batch.valid, p.inv_temperature)
-        adv, count, diag = self.diagnostics(logp, batch.logp_roll, batch.valid, batch.cu_rows, batch.rewards,
-                                            batch.shape.group_size, p)
+        # Alg. 1 estimates the coefficient from log pi_train at the checkpoint that generated the rollout
+        adv, count, diag = self.diagnostics(logp if logp_old is None else logp_old, batch.logp_roll, batch.valid,
+                                            batch.cu_rows, batch.rewards, batch.shape.group_size, p)
         loss, wtilde, dz = self.grpo_loss_grad(batch.logits, batch.token_ids, batch.valid, batch.cu_rows, logp, lse,
                                                batch.logp_roll, adv, count, diag, p, logp_old, logp_ref,
                                                dlogits=batch.logits if in_place else None)
@@ -252,14 +268,15 @@ class AisContext:
     # ------------------------------------------------------------------ one-sweep variant
     def token_logprob_softmax_grad(self, logits, token_ids, valid=None, inv_temperature: float = 1.0, sgrad=None):
         """-> (logp, lse, sgrad) with sgrad[n, v] = softmax_v - 1[v = y_n]; pass sgrad=logits for in place."""
-        n_rows, vocab, row_stride = _logits_geometry(logits)
         dev = self.device
+        n_rows, vocab, row_stride = _logits_geometry(logits, dev)
         logp = torch.empty(n_rows, dtype=torch.float32, device=dev)
         lse = torch.empty(n_rows, dtype=torch.float32, device=dev)
         if sgrad is None:
             sgrad = torch.empty_strided(logits.shape, logits.stride(), dtype=logits.dtype, device=dev)
         elif sgrad.dtype != logits.dtype or sgrad.shape != logits.shape or sgrad.stride() != logits.stride():
             raise ValueError("sgrad must have the dtype, shape and strides of logits")
+        _dev_ptr(sgrad, dev, "sgrad")
         self._sync_stream()
         rc = self._lib.ais_token_logprob_softmax_grad(
             self._h, C.c_void_p(logits.data_ptr()), _dtype_code(logits), n_rows, vocab, row_stride,
@@ -296,8 +313,8 @@ class AisContext:
         p = params or default_params()
         logp, lse, s = self.token_logprob_softmax_grad(batch.logits, batch.token_ids, batch.valid, p.inv_temperature,
                                                        sgrad=batch.logits if in_place else None)
-        adv, count, diag = self.diagnostics(logp, batch.logp_roll, batch.valid, batch.cu_rows, batch.rewards,
-                                            batch.shape.group_size, p)
+        adv, count, diag = self.diagnostics(logp if logp_old is None else logp_old, batch.logp_roll, batch.valid,
+                                            batch.cu_rows, batch.rewards, batch.shape.group_size, p)
         loss, wtilde, g = self.grpo_row_scale(logp, batch.logp_roll, batch.valid, batch.cu_rows, adv, count, diag, p,
                                               logp_old, logp_ref)
         return dict(logp=logp, lse=lse, adv=adv, count=count, diag=diag, loss=loss, wtilde=wtilde, sgrad=s, g=g)
@@ -305,7 +322,7 @@ class AisContext:
     # ------------------------------------------------------------------ FP8 rollout perturbation
     def fp8_quantize_rows(self, logits):
         """-> (codes [R, V] uint8, scale [R] fp32).  See ais_fp8_quantize_rows in include/ais.h."""
-        n_rows, vocab, row_stride = _logits_geometry(logits)
+        n_rows, vocab, row_stride = _logits_geometry(logits, self.device)
         codes = torch.empty((n_rows, vocab), dtype=torch.uint8, device=self.device)
         scale = torch.empty(n_rows, dtype=torch.float32, device=self.device)
         self._sync_stream()
@@ -317,10 +334,15 @@ class AisContext:
 
     def fp8_dequantize_rows(self, codes, scale, dtype=torch.float32):
         """-> z_r [R, V] of `dtype` (float32 or bfloat16)."""
+        if codes.dim() != 2 or codes.stride(1) != 1 and codes.shape[1] > 1:
+            raise ValueError("codes must be [n_rows, vocab] with unit stride along the vocabulary")
+        if codes.dtype != torch.uint8:
+            raise TypeError(f"codes: expected torch.uint8, got {codes.dtype}")
+        codes_ptr = _dev_ptr(codes, self.device, "codes")
         n_rows, vocab = codes.shape
         out = torch.empty((n_rows, vocab), dtype=dtype, device=self.device)
         self._sync_stream()
-        rc = self._lib.ais_fp8_dequantize_rows(self._h, _ptr(codes, torch.uint8, None, "codes", self.device),
+        rc = self._lib.ais_fp8_dequantize_rows(self._h, codes_ptr,
                                                codes.stride(0) if n_rows > 1 else vocab,
                                                _ptr(scale, torch.float32, n_rows, "scale", self.device), n_rows,
                                                vocab, _ptr(out), _dtype_code(out), vocab)
@@ -330,7 +352,7 @@ class AisContext:
 
     def fp8_rollout_logprob(self, logits, token_ids, valid=None):
         """-> logp_roll [R] fp32: log-softmax of the FP8 round trip of each row at the sampled token."""
-        n_rows, vocab, row_stride = _logits_geometry(logits)
+        n_rows, vocab, row_stride = _logits_geometry(logits, self.device)
         out = torch.empty(n_rows, dtype=torch.float32, device=self.device)
         self._sync_stream()
         rc = self._lib.ais_fp8_rollout_logprob(
@@ -349,6 +371,7 @@ class AisContext:
                 raise ValueError(f"{name} must be 2-D with unit stride along d_model")
             if t.dtype != torch.bfloat16:
                 raise ValueError(f"{name} must be bfloat16")
+            _dev_ptr(t, self.device, name)
         n_rows, d_model = hidden.shape
         vocab = weight.shape[0]
         if weight.shape[1] != d_model:
@@ -396,6 +419,10 @@ class AisContext:
         nbytes = src.numel() * src.element_size()
         if dst.numel() * dst.element_size() != nbytes:
             raise ValueError("size mismatch")
+        if not (src.is_contiguous() and dst.is_contiguous()):
+            raise ValueError("copy needs contiguous tensors")
+        _dev_ptr(dst, self.device, "dst")
+        _dev_ptr(src, self.device, "src")
         self._sync_stream()
         rc = self._lib.ais_copy(self._h, C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), nbytes)
         if rc != 0:

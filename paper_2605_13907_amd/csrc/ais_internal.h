@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <vector>
 
 #include "ais.h"
@@ -65,12 +66,32 @@ struct ais_ctx {
   struct Timed { hipEvent_t start, stop; int which; };
   std::vector<Timed> timed;      // events of measured launches
   std::vector<hipEvent_t> pool;  // recycled events
+  // The row tiling that the last ais_diagnostics call left in the workspace (tile_off and a ticket counter that is
+  // back at zero).  The calls that follow it in a step reuse the tiling instead of launching the plan kernel again
+  // when they name the same cu_rows array, sizes and stream; anything else that writes the workspace clears it.
+  struct Plan {
+    const long long* cu_rows = nullptr;
+    long long n_rows = -1;
+    int n_resp = -1;
+    hipStream_t stream = nullptr;
+    bool valid = false;
+  } plan;
 };
 
 namespace ais {
 
 int ensure_workspace(ais_ctx* ctx, size_t bytes);
 int hip_fail(ais_ctx* ctx, hipError_t e);
+
+// Raises the dynamic-LDS limit of kernel `fn` to `bytes` on the context's device, once per (kernel, device): `once`
+// and `ok` are the caller's function-local tables of kMaxDevices entries.  False if the runtime refuses.
+inline bool allow_dynamic_lds(ais_ctx* ctx, const void* fn, int bytes, std::once_flag* once, bool* ok) {
+  std::call_once(once[ctx->device], [&] {
+    ok[ctx->device] = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess;
+    if (!ok[ctx->device]) (void)hipGetLastError();
+  });
+  return ok[ctx->device];
+}
 
 // Brackets one launch with events when profiling is on.
 struct ScopedTimer {

@@ -15,6 +15,7 @@ int hip_fail(ais_ctx* ctx, hipError_t e) {
 
 int ensure_workspace(ais_ctx* ctx, size_t bytes) {
   if (bytes <= ctx->ws_bytes) return AIS_OK;
+  ctx->plan.valid = false;             // the tiling lived in the block that is about to be replaced
   // growing is rare (first call at a new size); it waits for queued work that may still use the old block
   hipError_t e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return hip_fail(ctx, e);
@@ -101,6 +102,30 @@ int check_batch(long long n_rows, int n_resp, int group_size) {
   if (n_resp < 1 || n_resp > (1 << 24)) return AIS_ERR_SIZE;
   if (group_size < 1) return AIS_ERR_SIZE;
   if (n_resp % group_size != 0) return AIS_ERR_GROUP;
+  return AIS_OK;
+}
+
+// Launches the plan kernel unless the tiling the last ais_diagnostics call left in the workspace is the one wanted.
+int plan_for_step(ais_ctx* ctx, const long long* cu_rows, int n_resp, long long n_rows, int* tile_off, int max_tiles) {
+  const ais_ctx::Plan& k = ctx->plan;
+  if (k.valid && k.cu_rows == cu_rows && k.n_rows == n_rows && k.n_resp == n_resp && k.stream == ctx->stream)
+    return AIS_OK;
+  ctx->plan.valid = false;
+  return launch_plan(ctx, cu_rows, n_resp, n_rows, tile_off, max_tiles);
+}
+
+int check_diagnostics_args(const float* logp_train, const float* logp_roll, long long n_rows,
+                           const long long* cu_rows, int n_resp, int group_size, const float* rewards,
+                           const ais_params* params, const float* adv_out, const int* count_out,
+                           const ais_diag* diag_out) {
+  int rc = check_batch(n_rows, n_resp, group_size);
+  if (rc != AIS_OK) return rc;
+  rc = check_params(params);
+  if (rc != AIS_OK) return rc;
+  if (cu_rows == nullptr || rewards == nullptr || adv_out == nullptr || count_out == nullptr ||
+      diag_out == nullptr)
+    return AIS_ERR_NULL;
+  if (n_rows > 0 && (logp_train == nullptr || logp_roll == nullptr)) return AIS_ERR_NULL;
   return AIS_OK;
 }
 
@@ -228,14 +253,9 @@ int ais_diagnostics(ais_ctx* ctx, const float* logp_train, const float* logp_rol
                     long long n_rows, const long long* cu_rows, int n_resp, int group_size,
                     const float* rewards, const ais_params* params, float* adv_out, int* count_out,
                     ais_diag* diag_out) {
-  int rc = check_batch(n_rows, n_resp, group_size);
+  int rc = check_diagnostics_args(logp_train, logp_roll, n_rows, cu_rows, n_resp, group_size, rewards, params, adv_out,
+                                  count_out, diag_out);
   if (rc != AIS_OK) return rc;
-  rc = check_params(params);
-  if (rc != AIS_OK) return rc;
-  if (cu_rows == nullptr || rewards == nullptr || adv_out == nullptr || count_out == nullptr ||
-      diag_out == nullptr)
-    return AIS_ERR_NULL;
-  if (n_rows > 0 && (logp_train == nullptr || logp_roll == nullptr)) return AIS_ERR_NULL;
   if (ctx == nullptr) return AIS_ERR_NULL;
   DeviceGuard guard(ctx->device);
   const WorkspaceLayout w = workspace_layout(n_rows, n_resp);
@@ -243,11 +263,20 @@ int ais_diagnostics(ais_ctx* ctx, const float* logp_train, const float* logp_rol
   if (rc != AIS_OK) return rc;
   char* ws = static_cast<char*>(ctx->ws);
   int* tile_off = reinterpret_cast<int*>(ws + w.tile_off);
+  ctx->plan.valid = false;
   rc = launch_plan(ctx, cu_rows, n_resp, n_rows, tile_off, w.max_tiles);
   if (rc != AIS_OK) return rc;
-  return launch_diagnostics(ctx, logp_train, logp_roll, valid, n_rows, cu_rows, n_resp, group_size, rewards,
-                            *params, tile_off, w.max_tiles, reinterpret_cast<DiagPartial*>(ws + w.partial),
-                            adv_out, count_out, diag_out);
+  rc = launch_diagnostics(ctx, logp_train, logp_roll, valid, n_rows, cu_rows, n_resp, group_size, rewards, *params,
+                          tile_off, w.max_tiles, reinterpret_cast<DiagPartial*>(ws + w.partial), adv_out, count_out,
+                          diag_out);
+  if (rc != AIS_OK) return rc;
+  // the tiling stays in the workspace for the calls that complete this step
+  ctx->plan.cu_rows = cu_rows;
+  ctx->plan.n_rows = n_rows;
+  ctx->plan.n_resp = n_resp;
+  ctx->plan.stream = ctx->stream;
+  ctx->plan.valid = true;
+  return AIS_OK;
 }
 
 int ais_grpo_loss_grad(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, long long vocab,
@@ -276,7 +305,7 @@ int ais_grpo_loss_grad(ais_ctx* ctx, const void* logits, ais_dtype dtype, long l
   char* ws = static_cast<char*>(ctx->ws);
   int* tile_off = reinterpret_cast<int*>(ws + w.tile_off);
   float* g = reinterpret_cast<float*>(ws + w.g);
-  rc = launch_plan(ctx, cu_rows, n_resp, n_rows, tile_off, w.max_tiles);
+  rc = plan_for_step(ctx, cu_rows, n_resp, n_rows, tile_off, w.max_tiles);
   if (rc != AIS_OK) return rc;
   rc = launch_row_coeff(ctx, logp_train, logp_roll, logp_old, logp_ref, valid, n_rows, cu_rows, n_resp, adv, count,
                         diag, *params, tile_off, w.max_tiles, reinterpret_cast<double*>(ws + w.partial), g,
@@ -329,7 +358,7 @@ int ais_grpo_row_scale(ais_ctx* ctx, const float* logp_train, const float* logp_
   if (rc != AIS_OK) return rc;
   char* ws = static_cast<char*>(ctx->ws);
   int* tile_off = reinterpret_cast<int*>(ws + w.tile_off);
-  rc = launch_plan(ctx, cu_rows, n_resp, n_rows, tile_off, w.max_tiles);
+  rc = plan_for_step(ctx, cu_rows, n_resp, n_rows, tile_off, w.max_tiles);
   if (rc != AIS_OK) return rc;
   return launch_row_coeff(ctx, logp_train, logp_roll, logp_old, logp_ref, valid, n_rows, cu_rows, n_resp, adv, count,
                           diag, *params, tile_off, w.max_tiles, reinterpret_cast<double*>(ws + w.partial), g_out,
@@ -398,6 +427,7 @@ int ais_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long hidden_strid
   const size_t per = sizeof(float) * (size_t)n_rows;
   int rc = ensure_workspace(ctx, per * (2 * (size_t)plan.max_chunks + 3) + 256);
   if (rc != AIS_OK) return rc;
+  ctx->plan.valid = false;             // this call's partials overwrite whatever tiling the workspace held
   float* part_m = static_cast<float*>(ctx->ws);
   float* part_s = part_m + (size_t)plan.max_chunks * (size_t)n_rows;
   float* zy = part_s + (size_t)plan.max_chunks * (size_t)n_rows;

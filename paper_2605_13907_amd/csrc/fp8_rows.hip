@@ -239,16 +239,10 @@ bool launch_rows(ais_ctx* ctx, const T* z, long long n_rows, int vocab, long lon
                  long long codes_stride, float* scale_out) {
   auto kernel = fp8_quantize_row_kernel<T, NV, NL, KFULL>;
   if (NL > 0) {
-    static bool attr_set_on[kMaxDevices] = {};             // the attribute belongs to the function on one device
-    bool& attr_set = attr_set_on[ctx->device];
-    if (!attr_set) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              NL * kSlotBytes) != hipSuccess) {
-        (void)hipGetLastError();
-        return false;                              // the caller falls back to the streaming kernel
-      }
-      attr_set = true;
-    }
+    static std::once_flag once[kMaxDevices];               // the attribute belongs to the function on one device
+    static bool ok[kMaxDevices];
+    if (!allow_dynamic_lds(ctx, reinterpret_cast<const void*>(kernel), NL * kSlotBytes, once, ok))
+      return false;                                // the caller falls back to the streaming kernel
   }
   kernel<<<dim3((unsigned)n_rows), dim3(kRowThreads), NL * kSlotBytes, ctx->stream>>>(z, row_stride, vocab, codes,
                                                                                        codes_stride, scale_out);

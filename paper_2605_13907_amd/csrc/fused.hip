@@ -246,14 +246,10 @@ int launch_nv(ais_ctx* ctx, const T* z, long long n_rows, int vocab, long long r
               const unsigned char* valid, float inv_t, float* logp, float* lse, T* sgrad) {
   auto kernel = fused_logprob_softmax_kernel<T, NV, NL, KFULL>;
   if (NL > 0) {
-    static bool attr_set_on[kMaxDevices] = {};             // the attribute belongs to the function on one device
-    bool& attr_set = attr_set_on[ctx->device];
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, NL * kSlotBytes);
-      if (e != hipSuccess) return hip_fail(ctx, e);
-      attr_set = true;
-    }
+    static std::once_flag once[kMaxDevices];               // the attribute belongs to the function on one device
+    static bool ok[kMaxDevices];
+    if (!allow_dynamic_lds(ctx, reinterpret_cast<const void*>(kernel), NL * kSlotBytes, once, ok))
+      return hip_fail(ctx, hipErrorInvalidValue);
   }
   kernel<<<dim3((unsigned)n_rows), dim3(kRowThreads), NL * kSlotBytes, ctx->stream>>>(
       z, row_stride, vocab, token_ids, valid, inv_t, logp, lse, sgrad, ctx->status_dev);

@@ -685,17 +685,13 @@ int launch_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long ld_h, con
                            float* part_m, float* part_s, float* zy, int* row_index, int* row_pos, void* dev_plan,
                            float* logp_out, float* lse_out) {
   constexpr int kStreamLds = AIS_LM_STAGES * kStStageBytes;
-  static bool attr_set_on[kMaxDevices] = {};                 // the attribute belongs to the function on one device
-  bool& attr_set = attr_set_on[ctx->device];
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_stream_kernel<AIS_LM_STAGES>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kStreamLds);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(lm_head_staged_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kLmLdsBytes);
-    if (e != hipSuccess) return hip_fail(ctx, e);
-    attr_set = true;
-  }
+  static std::once_flag once_stream[kMaxDevices], once_staged[kMaxDevices];   // per function and device
+  static bool ok_stream[kMaxDevices], ok_staged[kMaxDevices];
+  if (!allow_dynamic_lds(ctx, reinterpret_cast<const void*>(lm_head_stream_kernel<AIS_LM_STAGES>), kStreamLds,
+                         once_stream, ok_stream) ||
+      !allow_dynamic_lds(ctx, reinterpret_cast<const void*>(lm_head_staged_kernel), kLmLdsBytes, once_staged,
+                         ok_staged))
+    return hip_fail(ctx, hipErrorInvalidValue);
   // The grid covers the work items of the worst case; with fewer evaluated rows the device-side plan may use
   // more, shorter chunks, but never more items than that, and the workgroups left over leave at once.
   const int max_items = ((plan.n_tblocks * plan.n_chunks + 7) / 8) * 8;

@@ -33,7 +33,7 @@ __global__ __launch_bounds__(kTileThreads) void plan_kernel(const long long* __r
                                                             int* __restrict__ ticket) {
   __shared__ long long chunk_sum[kTileThreads];
   const int tid = threadIdx.x;
-  if (tid == 0) *ticket = 0;         // counts the finished workgroups of the reduction kernel that follows
+  if (tid == 0) *ticket = 0;         // counts the finished workgroups of each reduction kernel that follows
   const int per = (n_resp + kTileThreads - 1) / kTileThreads;
   const int i0 = min(n_resp, tid * per), i1 = min(n_resp, i0 + per);
   long long sum = 0;
@@ -200,6 +200,7 @@ __device__ __forceinline__ bool last_workgroup(int* ticket) {
   if (threadIdx.x == 0) {
     __threadfence();
     s_last = (atomicAdd(ticket, 1) == (int)gridDim.x - 1);
+    if (s_last) *ticket = 0;                 // every other workgroup has taken its ticket: ready for the next launch
   }
   __syncthreads();
   const bool last = s_last != 0;
@@ -388,9 +389,12 @@ __global__ __launch_bounds__(kTileThreads) void row_coeff_kernel(
       float g = 0.f, wt = 0.f;
       if (valid == nullptr || valid[n] != 0) {
         const double lt = (double)logp_train[n];
-        const double wbar = exp(fmin(lt - (double)logp_roll[n], lnC));
+        // the sampler-trainer ratio is taken at the checkpoint that generated the rollout (Alg. 1, "Sampler-Trainer
+        // ratio"; Sec. 3.2: the two ratios are orthogonal), the old-new ratio between that checkpoint and theta
+        const double l_old = logp_old != nullptr ? (double)logp_old[n] : lt;
+        const double wbar = exp(fmin(l_old - (double)logp_roll[n], lnC));
         const double wtilde = 1.0 + alpha * (wbar - 1.0);                       // Eq. 18 / Alg. 1 rectification weight
-        const double rho_on = logp_old != nullptr ? exp(lt - (double)logp_old[n]) : 1.0;
+        const double rho_on = logp_old != nullptr ? exp(lt - l_old) : 1.0;
         const double clipped = fmin(fmax(rho_on, lo_clip), hi_clip);
         // the unclipped branch is the minimum (ties included) iff the ratio has not left the trust
         // region on the side the advantage pushes towards

@@ -477,6 +477,37 @@ def pin_exact_expectation_is_policy_gradient(O):
     assert np.abs(pi_train @ (eye - pi_train[None, :])).max() < 1e-15
 
 
+def pin_sampler_trainer_ratio_at_rollout_checkpoint(O):
+    """Alg. 1 takes the sampler-trainer ratio at theta_old and Sec. 3.2 calls the two ratios orthogonal: with a
+    stale log pi_old, (a) a rollout engine without precision gap (log pi_roll = log pi_old) gives w_tilde = 1 for
+    any theta and any alpha, i.e. plain GRPO with its old-new ratio; (b) w_tilde, alpha and every diagnostic do not
+    move when theta does; (c) w_tilde equals 1 + alpha (min(exp(log pi_old - log pi_roll), C) - 1) row by row."""
+    z, y, valid, cu, _, rewards = _rand_batch(B=4, G=2, V=9, seed=91)
+    R = z.shape[0]
+    y[~valid] = 0
+    rng = np.random.default_rng(91)
+    logp0, _ = O.token_logprob(z, y, valid)
+    logp_old = logp0 + rng.normal(0, 0.3, size=R)
+    for alpha in (0.3, 1.0, -1.0):
+        p = O.Params(alpha_override=alpha)
+        out = O.ais_grpo(z, y, valid, cu, logp_old.copy(), rewards, 2, p, logp_old=logp_old)      # (a)
+        assert np.all(out["wtilde"][valid] == 1.0)
+        ref = O.ais_grpo(z, y, valid, cu, logp_old.copy(), rewards, 2, O.Params(alpha_override=0.0), logp_old=logp_old)
+        np.testing.assert_allclose(out["dz"], ref["dz"], rtol=1e-13, atol=1e-16)
+        assert np.abs(ref["dz"]).max() > 0
+    logp_roll = logp_old + rng.normal(0, 0.5, size=R)
+    p = O.Params()
+    a = O.ais_grpo(z, y, valid, cu, logp_roll, rewards, 2, p, logp_old=logp_old)
+    b = O.ais_grpo(z + rng.normal(0, 0.7, size=z.shape), y, valid, cu, logp_roll, rewards, 2, p, logp_old=logp_old)   # (b)
+    assert np.array_equal(a["wtilde"], b["wtilde"]) and a["diag"]["alpha"] == b["diag"]["alpha"] > 0
+    for k in ("mean_w", "cv2", "dbar", "dsigma", "alpha_ess", "alpha_mis", "alpha_var", "kl_roll_train"):
+        assert a["diag"][k] == b["diag"][k], k
+    assert not np.allclose(a["dz"], b["dz"])
+    want = 1.0 + a["diag"]["alpha"] * (np.minimum(np.exp(logp_old - logp_roll), p.C) - 1.0)              # (c)
+    np.testing.assert_allclose(a["wtilde"][valid], want[valid], rtol=1e-14)
+    assert np.abs(want[valid] - 1.0).max() > 0.05
+
+
 def pin_clip_region(O):
     """Tokens whose old-new ratio left the trust region on the penalised side get no gradient (Eq. 19):
     A > 0 and rho_on > 1 + eps, or A < 0 and rho_on < 1 - eps; on the other side the gradient is rho_on A w."""

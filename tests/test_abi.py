@@ -292,3 +292,39 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=300)
     assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
     assert not r.stdout.strip().startswith("{")              # no result line for a run that did not happen
+
+
+def test_binding_rejects_host_tensors_before_any_launch():
+    """A host (or foreign-device) tensor handed to a kernel would be a GPU memory fault, not an error code: the
+    binding must refuse every large buffer that is not on the context's GPU before it allocates or launches
+    anything.  No GPU is needed: the context object below has no library handle, so reaching a launch would raise
+    AttributeError instead of the expected ValueError."""
+    import torch
+
+    ctx = object.__new__(B.AisContext)
+    ctx.device = torch.device("cuda", 0)
+    ctx._h = None
+    ctx._lib = None
+    z = torch.zeros(4, 64, dtype=torch.bfloat16)
+    tok = torch.zeros(4, dtype=torch.int32)
+    f = torch.zeros(4)
+    with pytest.raises(ValueError, match="logits is on cpu"):
+        ctx.token_logprob(z, tok)
+    with pytest.raises(ValueError, match="logits is on cpu"):
+        ctx.token_logprob_softmax_grad(z, tok)
+    with pytest.raises(ValueError, match="logits is on cpu"):
+        ctx.grpo_loss_grad(z, tok, None, torch.zeros(3, dtype=torch.int64), f, f, f, torch.zeros(2),
+                           torch.zeros(2, dtype=torch.int32), torch.zeros(C.sizeof(B.AisDiag), dtype=torch.uint8))
+    with pytest.raises(ValueError, match="logits is on cpu"):
+        ctx.fp8_quantize_rows(z)
+    with pytest.raises(ValueError, match="logits is on cpu"):
+        ctx.fp8_rollout_logprob(z, tok)
+    with pytest.raises(ValueError, match="codes is on cpu"):
+        ctx.fp8_dequantize_rows(torch.zeros(4, 64, dtype=torch.uint8), f)
+    with pytest.raises(ValueError, match="hidden is on cpu"):
+        ctx.lm_head_logprob(z, torch.zeros(100, 64, dtype=torch.bfloat16), tok)
+    with pytest.raises(ValueError, match="dst is on cpu"):
+        ctx.copy(torch.zeros(16), torch.zeros(16))
+    with pytest.raises(ValueError):                         # the geometry helper itself, with and without a device
+        B._logits_geometry(torch.zeros(4, 8, 2), None)
+    assert B._logits_geometry(z, None) == (4, 64, 64)

@@ -53,6 +53,8 @@ MUTANTS = [
     ("wt = 1.0 + alpha * (_f64(wbar) - 1.0)", "wt = 1.0 + alpha * _f64(wbar)"),
     ("wt = 1.0 + alpha * (_f64(wbar) - 1.0)", "wt = alpha + (1.0 - alpha) * _f64(wbar)"),
     # O6
+    ("logp_at_rollout = logp if logp_old is None else _f64(logp_old)", "logp_at_rollout = logp"),
+    ("diag = diagnostics(logp if logp_old is None else logp_old, logp_roll", "diag = diagnostics(logp, logp_roll"),
     ("active = (unclipped <= clipped)", "active = (unclipped >= clipped)"),
     ("s = np.minimum(unclipped, clipped)", "s = np.maximum(unclipped, clipped)"),
     ("clipped = np.clip(rho_on, 1.0 - p.clip_eps, 1.0 + p.clip_eps) * a",
