@@ -88,12 +88,113 @@ def cpu_baseline(batch, params, sample_rows: int):
                             "sample": f"first {m} rows in one process, {dt1:.2f} s wall"}}
 
 
+def burst_class(vocab: int, esize: int) -> str:
+    """Name of the gradient-sweep instantiation that the library's launcher picks for 16-byte aligned rows of this
+    width (reporting only; mirrors the table in csrc/sweeps.hip: vectors per lane and burst, bursts, vectors that
+    surely exist)."""
+    per_vec = 16 // esize
+    need = (vocab // per_vec + 1023) // 1024
+    t = "bf16" if esize == 2 else "float"
+    if need <= 12:
+        nv = 4 * ((max(need, 1) + 3) // 4)
+        return f"dlogits_burst_kernel<{t}, {nv}, 1, {nv - 4}>"
+    if need <= 20:
+        return f"dlogits_burst_kernel<{t}, {need}, 1, {need - 1}>"
+    if need <= 32:
+        return f"dlogits_burst_kernel<{t}, 16, 2, 20>"
+    if need <= 48:
+        return f"dlogits_burst_kernel<{t}, 16, 3, 32>"
+    return f"dlogits_burst_kernel<{t}, 16, 0, 0>"
+
+
+def time_workload(torch, binding, workloads, ctx, k, steps, warmup, mode="ais", stale_old=False, in_place=False):
+    """Generates workload k, runs `warmup` untimed and `steps` timed passes of the three-call path over it, and
+    returns (summary dict, batch, params, output buffer, step function, logp_old)."""
+    shape = workloads.config(k)
+    t0 = time.perf_counter()
+    batch = workloads.generate(shape, "cuda", row_chunk=512)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t0
+    R, V = batch.logits.shape
+    N = batch.n_valid
+    e = batch.logits.element_size()
+    p = binding.default_params(alpha_override={"ais": -1.0, "tis": 1.0, "grpo": 0.0}[mode])
+    dz = batch.logits if in_place else torch.empty_like(batch.logits)
+    logp_old = None
+    if stale_old:       # torch's log_softmax stands in for the trainer's earlier log-probs (not timed)
+        logp_old = torch.empty(R, dtype=torch.float32, device="cuda")
+        gen_old = torch.Generator(device="cuda").manual_seed(17)
+        for r0 in range(0, R, 512):
+            z = batch.logits[r0:r0 + 512].float()
+            tok = batch.token_ids[r0:r0 + 512].long().clamp(min=0).unsqueeze(1)
+            logp_old[r0:r0 + 512] = torch.log_softmax(z, 1).gather(1, tok).squeeze(1)
+        logp_old += 0.2 * torch.randn(R, device="cuda", generator=gen_old)
+
+    def step():
+        logp, lse = ctx.token_logprob(batch.logits, batch.token_ids, batch.valid, p.inv_temperature)
+        adv, count, diag = ctx.diagnostics(logp if logp_old is None else logp_old, batch.logp_roll, batch.valid,
+                                           batch.cu_rows, batch.rewards, shape.group_size, p)
+        return ctx.grpo_loss_grad(batch.logits, batch.token_ids, batch.valid, batch.cu_rows, logp, lse,
+                                  batch.logp_roll, adv, count, diag, p, logp_old=logp_old, dlogits=dz), diag
+
+    if in_place:
+        keep = batch.logits.clone()
+    for _ in range(warmup):
+        step()
+        if in_place:
+            batch.logits.copy_(keep)
+    torch.cuda.synchronize()
+    ctx.profile(True)
+    t_total = 0.0
+    if in_place:                 # the logits have to be restored between steps: time each step on its own
+        for _ in range(steps):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            (loss, _, _), diag = step()
+            torch.cuda.synchronize()
+            t_total += time.perf_counter() - t0
+            batch.logits.copy_(keep)
+    else:                        # exactly K steps between two synchronisations
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            (loss, _, _), diag = step()
+        torch.cuda.synchronize()
+        t_total = time.perf_counter() - t0
+    ms_fwd, n_fwd = ctx.profile_read(binding.AIS_K_LOGPROB)
+    ms_bwd, n_bwd = ctx.profile_read(binding.AIS_K_DLOGITS)
+    ctx.profile(False)
+    d = ctx.read_diag(diag)
+    assert ctx.status() == 0
+    ms_step = t_total / steps * 1e3
+    fwd_bytes = e * V * N                                   # one read of every valid row
+    bwd_bytes = 2 * e * V * N + e * V * (R - N)             # read + write of valid rows, zero-fill of the others
+    fwd_gbps = fwd_bytes / (ms_fwd / n_fwd * 1e-3) / 1e9
+    bwd_gbps = bwd_bytes / (ms_bwd / n_bwd * 1e-3) / 1e9
+    path_gbps = (fwd_bytes + bwd_bytes) / (ms_step * 1e-3) / 1e9
+    summary = {
+        "k": k, "workload": f"config {k}: {shape.name}", "vocab": V, "rows": R, "valid_rows": N, "responses": shape.n_resp,
+        "group_size": shape.group_size, "logits": shape.logits_dtype, "layout": shape.layout,
+        "ms_per_step": ms_step, "tokens_per_s": N / (ms_step * 1e-3),
+        "path_hbm": {"GB/s": path_gbps, "frac": path_gbps / HBM_PEAK_GBPS, "bytes_per_step": fwd_bytes + bwd_bytes},
+        "dominant_kernel": {"name": burst_class(V, e), "avg_ms": ms_bwd / n_bwd, "bytes_per_launch": bwd_bytes,
+                            "GB/s": bwd_gbps, "frac": bwd_gbps / HBM_PEAK_GBPS,
+                            "zero_filled_rows": R - N},
+        "token_logprob": {"avg_ms": ms_fwd / n_fwd, "GB/s": fwd_gbps, "frac": fwd_gbps / HBM_PEAK_GBPS},
+        "diag": {q: d[q] for q in ("alpha", "alpha_ess", "alpha_mis", "alpha_var", "dbar", "ess_ratio")},
+        "loss": float(loss.item()), "gen_s": t_gen,
+    }
+    return summary, batch, p, dz, logp_old
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = Qwen3-8B-shaped, V = 151,936)")
+    ap.add_argument("--config", type=int, default=2, help="headline workload 1..5 (2 = Qwen3-8B-shaped, V = 151,936)")
+    ap.add_argument("--others", type=str, default="1,3,4,5",
+                    help="workloads also timed and listed under `workloads` (comma-separated, empty = none)")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="rows of the batch the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--in-place", action="store_true", help="write the gradient over the logits")
     ap.add_argument("--extras", action="store_true",
@@ -112,64 +213,26 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    shape = workloads.config(args.config)
-    t0 = time.perf_counter()
-    batch = workloads.generate(shape, "cuda", row_chunk=512)
-    torch.cuda.synchronize()
-    t_gen = time.perf_counter() - t0
-    R, V = batch.logits.shape
-    N = batch.n_valid
-    e = batch.logits.element_size()
     ctx = binding.AisContext()
-    p = binding.default_params(alpha_override={"ais": -1.0, "tis": 1.0, "grpo": 0.0}[args.mode])
-    dz = batch.logits if args.in_place else torch.empty_like(batch.logits)
-    logp_old = None
-    if args.stale_old:       # torch's log_softmax stands in for the trainer's earlier log-probs (not timed)
-        logp_old = torch.empty(R, dtype=torch.float32, device="cuda")
-        gen_old = torch.Generator(device="cuda").manual_seed(17)
-        for r0 in range(0, R, 512):
-            z = batch.logits[r0:r0 + 512].float()
-            tok = batch.token_ids[r0:r0 + 512].long().clamp(min=0).unsqueeze(1)
-            logp_old[r0:r0 + 512] = torch.log_softmax(z, 1).gather(1, tok).squeeze(1)
-        logp_old += 0.2 * torch.randn(R, device="cuda", generator=gen_old)
 
-    def step():
-        logp, lse = ctx.token_logprob(batch.logits, batch.token_ids, batch.valid, p.inv_temperature)
-        adv, count, diag = ctx.diagnostics(logp, batch.logp_roll, batch.valid, batch.cu_rows, batch.rewards,
-                                           shape.group_size, p)
-        return ctx.grpo_loss_grad(batch.logits, batch.token_ids, batch.valid, batch.cu_rows, logp, lse,
-                                  batch.logp_roll, adv, count, diag, p, logp_old=logp_old, dlogits=dz), diag
+    # the other workloads first (each generated, timed and released), the headline workload last so that its batch
+    # is the one the extras and the CPU baseline work on
+    others = []
+    for k in [int(x) for x in args.others.split(",") if x.strip()]:
+        if k == args.config:
+            continue
+        summary, batch, p, dz, _ = time_workload(torch, binding, workloads, ctx, k, args.steps, args.warmup, args.mode)
+        others.append(summary)
+        del batch, dz
+        torch.cuda.empty_cache()
 
-    if args.in_place:
-        keep = batch.logits.clone()
-
-    for _ in range(args.warmup):
-        step()
-        if args.in_place:
-            batch.logits.copy_(keep)
-    torch.cuda.synchronize()
-    ctx.profile(True)
-    t_total = 0.0
-    if args.in_place:            # the logits have to be restored between steps: time each step on its own
-        for _ in range(args.steps):
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            (loss, _, _), diag = step()
-            torch.cuda.synchronize()
-            t_total += time.perf_counter() - t0
-            batch.logits.copy_(keep)
-    else:                        # exactly K steps between two synchronisations
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            (loss, _, _), diag = step()
-        torch.cuda.synchronize()
-        t_total = time.perf_counter() - t0
-    ms_fwd, n_fwd = ctx.profile_read(binding.AIS_K_LOGPROB)
-    ms_bwd, n_bwd = ctx.profile_read(binding.AIS_K_DLOGITS)
-    ctx.profile(False)
-    d = ctx.read_diag(diag)
-    assert ctx.status() == 0
+    head, batch, p, dz, logp_old = time_workload(torch, binding, workloads, ctx, args.config, args.steps, args.warmup,
+                                                 args.mode, args.stale_old, args.in_place)
+    shape = batch.shape
+    R, V = batch.logits.shape
+    N = head["valid_rows"]
+    e = batch.logits.element_size()
+    ms_step = head["ms_per_step"]
 
     # plain copy of the logits: what this device's HBM sustains for a read+write stream
     ctx.profile(True)
@@ -180,32 +243,29 @@ def main():
     ctx.profile(False)
     copy_gbps = 2.0 * R * V * e / (ms_copy / n_copy * 1e-3) / 1e9
 
-    ms_step = t_total / args.steps * 1e3
-    fwd_bytes = e * V * N                                   # one read of every valid row
-    bwd_bytes = 2 * e * V * N + e * V * (R - N)             # read + write of valid rows, zero-fill of the others
-    fwd_gbps = fwd_bytes / (ms_fwd / n_fwd * 1e-3) / 1e9
-    bwd_gbps = bwd_bytes / (ms_bwd / n_bwd * 1e-3) / 1e9
-    path_gbps = (fwd_bytes + bwd_bytes) / (ms_step * 1e-3) / 1e9
+    dom = head["dominant_kernel"]
     result = {
-        "metric": "fused_logprob_ais_grad_tokens_per_s", "value": N / (ms_step * 1e-3), "unit": "tokens/s",
+        "metric": "fused_logprob_ais_grad_tokens_per_s", "value": head["tokens_per_s"], "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"config {args.config}: {shape.name}", "vocab": V, "rows": R, "valid_rows": N,
+        "dtype": shape.logits_dtype, "arithmetic": "f32 on the logits' storage type; f64 in the batch reductions",
+        "data": "synthetic",
+        "config": {"workload": head["workload"], "vocab": V, "rows": R, "valid_rows": N,
                    "responses": shape.n_resp, "group_size": shape.group_size, "logits": shape.logits_dtype,
                    "layout": shape.layout, "in_place": bool(args.in_place), "mode": args.mode,
                    "stale_old_policy": bool(args.stale_old)},
-        "roofline": {"bound": "hbm", "kernel": "dlogits_burst_kernel", "achieved": bwd_gbps, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": bwd_gbps / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": dom["name"], "achieved": dom["GB/s"], "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": dom["frac"],
                      "traffic": measured_traffic("dlogits_burst_kernel", args.config),
-                     "avg_ms": ms_bwd / n_bwd, "bytes_per_launch": bwd_bytes},
-        "kernels": {"token_logprob": {"avg_ms": ms_fwd / n_fwd, "GB/s": fwd_gbps, "frac": fwd_gbps / HBM_PEAK_GBPS},
-                    "dlogits": {"avg_ms": ms_bwd / n_bwd, "GB/s": bwd_gbps, "frac": bwd_gbps / HBM_PEAK_GBPS},
+                     "avg_ms": dom["avg_ms"], "bytes_per_launch": dom["bytes_per_launch"]},
+        "kernels": {"token_logprob": head["token_logprob"],
+                    "dlogits": {q: dom[q] for q in ("avg_ms", "GB/s", "frac")},
                     "copy_yardstick": {"avg_ms": ms_copy / n_copy, "GB/s": copy_gbps}},
-        "path_hbm": {"GB/s": path_gbps, "frac": path_gbps / HBM_PEAK_GBPS,
-                     "bytes_per_step": fwd_bytes + bwd_bytes},
-        "diag": {k: d[k] for k in ("alpha", "alpha_ess", "alpha_mis", "alpha_var", "dbar", "ess_ratio")},
-        "loss": float(loss.item()), "gen_s": t_gen,
+        "path_hbm": head["path_hbm"],
+        "diag": head["diag"], "loss": head["loss"], "gen_s": head["gen_s"],
+        "workloads": [dict(w, dominant_kernel=dict(w["dominant_kernel"],
+                                                    traffic=measured_traffic("dlogits_burst_kernel", w["k"])))
+                      for w in others],
     }
     if args.extras:
         ctx.profile(True)

@@ -19,7 +19,7 @@ def ctx():
     c.close()
 
 
-def check_one_sweep(ctx, batch, p=None, logp_old=None, logp_ref=None, in_place=False):
+def check_one_sweep(ctx, batch, p=None, logp_old=None, logp_ref=None, in_place=False, strict=False):
     p = p or B.default_params()
     ref = P.run_oracle(batch, p, logp_old, logp_ref)
     valid = batch.valid.cpu().numpy().astype(bool)
@@ -34,25 +34,23 @@ def check_one_sweep(ctx, batch, p=None, logp_old=None, logp_ref=None, in_place=F
         chunks.append((r0, r1, dz, s_ref))
     out = ctx.step_one_sweep(batch, p, logp_old, logp_ref, in_place=in_place)
     torch.cuda.synchronize()
-    d = P.compare_scalars(ctx, out, ref, batch)
+    d = P.compare_scalars(ctx, out, ref, batch, strict)
     g = P.to_np64(out["g"])
     g_ref = ref["g"] * inv_t
     assert np.all(g[g_ref == 0] == 0)
     # the coefficient carries w_tilde, the on-policy ratio and the KL term: what the observed log-prob error E can do
     # to them (parity.compare_scalars leaves the per-row bound in ref["g_slack"]) is added to the relative tolerance
-    assert np.all(np.abs(g - g_ref) <= P.REL * np.abs(g_ref) + 1e-12 + ref["g_slack"] * inv_t), \
+    assert np.all(np.abs(g - g_ref) <= P.REL * np.abs(g_ref) + (0.0 if strict else 1e-12 + ref["g_slack"] * inv_t)), \
         f"g: worst {float(np.max(np.abs(g - g_ref)))!r}"
 
     for r0, r1, dz_ref, s_ref in chunks:
         s = P.to_np64(out["sgrad"][r0:r1, :V])
         assert np.all(s[~valid[r0:r1]] == 0), "rows that are not evaluated must have a zero direction"
-        floor = P.oracle_floor(valid[r0:r1].astype(np.float64), ref["lse"][r0:r1])
-        tol = P.DZ_REL * np.abs(s_ref) + P.DZ_CUSHION * np.abs(s_ref).max(axis=1, keepdims=True) + P.DZ_TINY + floor
+        tol = P.dz_tolerance(s_ref, valid[r0:r1].astype(np.float64), ref["lse"][r0:r1], strict)
         bad = np.abs(s - s_ref) > tol
         assert not bad.any(), f"direction mismatch rows {r0}:{r1} at {np.argwhere(bad)[0]}"
         prod = g[r0:r1, None] * s
-        floor = P.oracle_floor(ref["g"][r0:r1], ref["lse"][r0:r1]) + (ref["g_slack"][r0:r1] * inv_t)[:, None]
-        tol = P.DZ_REL * np.abs(dz_ref) + P.DZ_CUSHION * np.abs(dz_ref).max(axis=1, keepdims=True) + P.DZ_TINY + floor
+        tol = P.dz_tolerance(dz_ref, ref["g"][r0:r1], ref["lse"][r0:r1], strict, ref["g_slack"][r0:r1], inv_t)
         bad = np.abs(prod - dz_ref) > tol
         assert not bad.any(), f"g * s differs from dlogits in rows {r0}:{r1} at {np.argwhere(bad)[0]}"
     assert ctx.status() == 0
@@ -64,11 +62,11 @@ def test_full_vocab(ctx, k, len_div):
     """Real row geometry: 151,936 (19 vector slots per lane, all in registers), 126,464 (16), and 248,320
     (31 slots: 22 in registers, 9 in LDS)."""
     shape = W.config(k).scaled(len_div=len_div, n_prompts=2 if k == 3 else None)
-    check_one_sweep(ctx, W.generate(shape, "cuda", row_chunk=128))
+    check_one_sweep(ctx, W.generate(shape, "cuda", row_chunk=128), strict=True)
 
 
 def test_tiny_fp32(ctx):
-    check_one_sweep(ctx, W.generate(W.config(1), "cuda"))
+    check_one_sweep(ctx, W.generate(W.config(1), "cuda"), strict=True)
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
