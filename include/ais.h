@@ -69,7 +69,8 @@ typedef enum ais_error {
   AIS_ERR_GROUP = -6,   /* n_resp is not a positive multiple of group_size             */
   AIS_ERR_DTYPE = -7,   /* unknown ais_dtype                                           */
   AIS_ERR_HIP = -8,     /* a HIP runtime call failed (see ais_last_hip_error)          */
-  AIS_ERR_NOMEM = -9    /* workspace allocation failed                                 */
+  AIS_ERR_NOMEM = -9,   /* workspace allocation failed                                 */
+  AIS_ERR_SCRATCH = -10 /* the batch needs more than the static scratch array holds    */
 } ais_error;
 
 /* Bits of the device status word. */
@@ -170,6 +171,24 @@ int ais_diagnostics(ais_ctx* ctx, const float* logp_train, const float* logp_rol
                     const unsigned char* valid, long long n_rows, const long long* cu_rows,
                     int n_resp, int group_size, const float* rewards, const ais_params* params,
                     float* adv_out, int* count_out, ais_diag* diag_out);
+
+/* ais_diagnostics for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical results; the row tiling,
+ * the ticket counter and the per-tile partials live in a static device array of AIS_STATIC_SCRATCH_BYTES that every
+ * GPU the library runs on holds until the process ends, so the call allocates nothing, frees nothing and never
+ * waits for the stream, whatever sizes came before.
+ *   Limit      56 * (ceil(n_rows / 1024) + n_resp) + 4 * (n_resp + 2) bytes, each part rounded up to 256, must fit
+ *              the array: e.g. 18 million rows in 512 responses, or 1 million rows in 16,000 responses.  Beyond
+ *              that the call returns AIS_ERR_SCRATCH and launches nothing.
+ *   Sharing    every call on one GPU, from any context, uses that GPU's one array (the kernels overwrite what they
+ *              read, so earlier contents do not matter): calls that overlap in time on one GPU race, also across
+ *              contexts and streams.  The row tiling it leaves behind is not reused by the calls that follow.
+ * Errors: as ais_diagnostics, plus AIS_ERR_SCRATCH. */
+#define AIS_STATIC_SCRATCH_BYTES (1 << 20)
+int ais_diagnostics_static(ais_ctx* ctx, const float* logp_train, const float* logp_roll,
+                           const unsigned char* valid, long long n_rows, const long long* cu_rows,
+                           int n_resp, int group_size, const float* rewards, const ais_params* params,
+                           float* adv_out, int* count_out, ais_diag* diag_out);
 
 /* Loss and gradient (Alg. 1, "Advantage Rectification" and "Policy Update"; Eq. 18, 19).
  * The two ratios of Sec. 3.2 are kept apart: the sampler-trainer ratio is taken at the checkpoint theta_old that

@@ -25,7 +25,9 @@ STATUS_BAD_TOKEN, STATUS_BAD_CU = 1, 2
 ERRORS = {
     0: "AIS_OK", -1: "AIS_ERR_NULL", -2: "AIS_ERR_SIZE", -3: "AIS_ERR_STRIDE", -4: "AIS_ERR_ALIGN",
     -5: "AIS_ERR_PARAM", -6: "AIS_ERR_GROUP", -7: "AIS_ERR_DTYPE", -8: "AIS_ERR_HIP", -9: "AIS_ERR_NOMEM",
+    -10: "AIS_ERR_SCRATCH",
 }
+STATIC_SCRATCH_BYTES = 1 << 20
 
 
 class AisParams(C.Structure):
@@ -67,6 +69,7 @@ SYMBOLS = {
     "ais_version": (_I, []),
     "ais_token_logprob": (_I, [_P, _P, _I, _LL, _LL, _LL, _P, _P, _F, _P, _P]),
     "ais_diagnostics": (_I, [_P, _P, _P, _P, _LL, _P, _I, _I, _P, C.POINTER(AisParams), _P, _P, _P]),
+    "ais_diagnostics_static": (_I, [_P, _P, _P, _P, _LL, _P, _I, _I, _P, C.POINTER(AisParams), _P, _P, _P]),
     "ais_grpo_loss_grad": (_I, [_P, _P, _I, _LL, _LL, _LL, _P, _P, _P, _I, _P, _P, _P, _P, _P, _P, _P, _P,
                                 C.POINTER(AisParams), _P, _P, _P]),
     "ais_token_logprob_softmax_grad": (_I, [_P, _P, _I, _LL, _LL, _LL, _P, _P, _F, _P, _P, _P]),
@@ -202,23 +205,31 @@ class AisContext:
         return logp, lse
 
     def diagnostics(self, logp_train, logp_roll, valid, cu_rows, rewards, group_size: int,
-                    params: Optional[AisParams] = None):
-        """-> (adv [B] fp32, count [B] int32, diag: uint8 tensor holding one ais_diag on the device)."""
+                    params: Optional[AisParams] = None, static_scratch: bool = False, out=None):
+        """-> (adv [B] fp32, count [B] int32, diag: uint8 tensor holding one ais_diag on the device).
+        static_scratch: call ais_diagnostics_static (no device allocation inside the library); out: the three
+        output tensors to write into instead of new ones (so that the binding allocates nothing either)."""
         p = params or default_params()
         dev = self.device
         n_rows = logp_train.numel()
         n_resp = rewards.numel()
-        adv = torch.empty(n_resp, dtype=torch.float32, device=dev)
-        count = torch.empty(n_resp, dtype=torch.int32, device=dev)
-        diag = torch.zeros(C.sizeof(AisDiag), dtype=torch.uint8, device=dev)
+        if out is None:
+            adv = torch.empty(n_resp, dtype=torch.float32, device=dev)
+            count = torch.empty(n_resp, dtype=torch.int32, device=dev)
+            diag = torch.zeros(C.sizeof(AisDiag), dtype=torch.uint8, device=dev)
+        else:
+            adv, count, diag = out
+            _ptr(adv, torch.float32, n_resp, "adv", dev), _ptr(count, torch.int32, n_resp, "count", dev)
+            _ptr(diag, torch.uint8, C.sizeof(AisDiag), "diag", dev)
         self._sync_stream()
-        rc = self._lib.ais_diagnostics(
+        fn = self._lib.ais_diagnostics_static if static_scratch else self._lib.ais_diagnostics
+        rc = fn(
             self._h, _ptr(logp_train, torch.float32, n_rows, "logp_train", dev),
             _ptr(logp_roll, torch.float32, n_rows, "logp_roll", dev), _ptr(valid, torch.uint8, n_rows, "valid", dev),
             n_rows, _ptr(cu_rows, torch.int64, n_resp + 1, "cu_rows", dev), n_resp, int(group_size),
             _ptr(rewards, torch.float32, n_resp, "rewards", dev), C.byref(p), _ptr(adv), _ptr(count), _ptr(diag))
         if rc != 0:
-            raise AisError(rc, "ais_diagnostics")
+            raise AisError(rc, "ais_diagnostics_static" if static_scratch else "ais_diagnostics")
         return adv, count, diag
 
     def grpo_loss_grad(self, logits, token_ids, valid, cu_rows, logp_train, lse, logp_roll, adv, count, diag,

@@ -76,6 +76,7 @@ struct ais_ctx {
     hipStream_t stream = nullptr;
     bool valid = false;
   } plan;
+  void* static_scratch = nullptr;   // address, on this context's device, of the library's static scratch array
 };
 
 namespace ais {

@@ -1,9 +1,15 @@
 // The C entry points: host-side argument checks, workspace, launches.  See include/ais.h for the contract.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "ais_internal.h"
+
+// Scratch memory of ais_diagnostics_static: every GPU the library runs on holds its own copy of this array, at its
+// own address, until the process ends.  In host code the name is only a handle for hipGetSymbolAddress, never an
+// address: each device's address is looked up once, in ais_create, and kept; kernels receive that pointer.
+static __device__ __align__(256) unsigned char scratch[AIS_STATIC_SCRATCH_BYTES];
 
 namespace ais {
 
@@ -105,6 +111,25 @@ int check_batch(long long n_rows, int n_resp, int group_size) {
   return AIS_OK;
 }
 
+// Address of the current device's copy of the static scratch array; looked up once per device.  The caller has
+// made `device` current.
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch_address(int device, void** out) {
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[device] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+      (void)hipGetLastError();
+      return AIS_ERR_HIP;
+    }
+    g_scratch_ptr[device] = ptr;
+  }
+  *out = g_scratch_ptr[device];
+  return AIS_OK;
+}
+
 // Launches the plan kernel unless the tiling the last ais_diagnostics call left in the workspace is the one wanted.
 int plan_for_step(ais_ctx* ctx, const long long* cu_rows, int n_resp, long long n_rows, int* tile_off, int max_tiles) {
   const ais_ctx::Plan& k = ctx->plan;
@@ -164,6 +189,7 @@ const char* ais_strerror(int err) {
     case AIS_ERR_DTYPE: return "unknown logits dtype";
     case AIS_ERR_HIP: return "a HIP runtime call failed";
     case AIS_ERR_NOMEM: return "workspace allocation failed";
+    case AIS_ERR_SCRATCH: return "the batch needs more than the static scratch array holds";
     default: return "unknown error";
   }
 }
@@ -195,7 +221,9 @@ int ais_create(ais_ctx** out, int device, void* hip_stream) {
   else
     (void)hipGetLastError();
   int rc = ensure_workspace(ctx, 1 << 20);
+  if (rc == AIS_OK) rc = guard.ok ? static_scratch_address(device, &ctx->static_scratch) : AIS_ERR_HIP;
   if (rc != AIS_OK) {
+    if (ctx->ws != nullptr) (void)hipFree(ctx->ws);
     (void)hipFree(ctx->status_dev);
     delete ctx;
     return rc;
@@ -277,6 +305,31 @@ int ais_diagnostics(ais_ctx* ctx, const float* logp_train, const float* logp_rol
   ctx->plan.stream = ctx->stream;
   ctx->plan.valid = true;
   return AIS_OK;
+}
+
+int ais_diagnostics_static(ais_ctx* ctx, const float* logp_train, const float* logp_roll,
+                           const unsigned char* valid, long long n_rows, const long long* cu_rows, int n_resp,
+                           int group_size, const float* rewards, const ais_params* params, float* adv_out,
+                           int* count_out, ais_diag* diag_out) {
+  int rc = check_diagnostics_args(logp_train, logp_roll, n_rows, cu_rows, n_resp, group_size, rewards, params, adv_out,
+                                  count_out, diag_out);
+  if (rc != AIS_OK) return rc;
+  // what the two kernels need: the tiling with its ticket counter, and one partial per tile (not the per-row
+  // coefficients of the gradient call, which come after them in the layout)
+  const WorkspaceLayout w = workspace_layout(n_rows, n_resp);
+  if (w.g > (size_t)AIS_STATIC_SCRATCH_BYTES) return AIS_ERR_SCRATCH;
+  if (ctx == nullptr) return AIS_ERR_NULL;
+  if (ctx->static_scratch == nullptr) return AIS_ERR_HIP;
+  DeviceGuard guard(ctx->device);
+  char* ws = static_cast<char*>(ctx->static_scratch);     // this device's address of the array, never its name
+  int* tile_off = reinterpret_cast<int*>(ws + w.tile_off);
+  // the plan kernel writes every tile_off entry this call reads and zeroes the ticket counter; every partial that
+  // level 2 reads is written by level 1 of the same launch: nothing of an earlier call's contents is used
+  rc = launch_plan(ctx, cu_rows, n_resp, n_rows, tile_off, w.max_tiles);
+  if (rc != AIS_OK) return rc;
+  return launch_diagnostics(ctx, logp_train, logp_roll, valid, n_rows, cu_rows, n_resp, group_size, rewards, *params,
+                            tile_off, w.max_tiles, reinterpret_cast<DiagPartial*>(ws + w.partial), adv_out, count_out,
+                            diag_out);
 }
 
 int ais_grpo_loss_grad(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, long long vocab,

@@ -47,7 +47,7 @@ def test_defaults_are_the_papers():
 def test_strerror_and_version():
     lib = B._lib()
     assert lib.ais_version() >= 1000
-    for code in range(0, -10, -1):
+    for code in range(0, -11, -1):
         assert len(lib.ais_strerror(code)) > 0
     assert lib.ais_strerror(0) == b"ok"
 
@@ -98,6 +98,30 @@ def test_diagnostics_argument_checks():
                 dict(adv_mode=2), dict(clip_eps=1.0), dict(inv_temperature=0.0), dict(beta_kl=-1.0),
                 dict(beta_var=float("nan"))):
         assert call_diag(params=B.default_params(**bad)) == -5, bad
+
+
+def test_static_diagnostics_argument_checks_and_size_limit():
+    """The entry point that allocates nothing: the argument checks of ais_diagnostics, and a documented error for
+    batches beyond what the static scratch array holds (checked before the context, so no GPU is needed)."""
+    lib = B._lib()
+    p = B.default_params()
+
+    def call(**kw):
+        a = dict(ctx=None, lt=FAKE, lr=FAKE, valid=None, n_rows=10, cu=FAKE, n_resp=8, G=4, rewards=FAKE,
+                 adv=FAKE, count=FAKE, diag=FAKE)
+        a.update(kw)
+        return lib.ais_diagnostics_static(a["ctx"], a["lt"], a["lr"], a["valid"], a["n_rows"], a["cu"], a["n_resp"],
+                                          a["G"], a["rewards"], C.byref(p), a["adv"], a["count"], a["diag"])
+
+    assert call() == -1                                   # everything fine except the NULL context
+    assert call(n_resp=0) == -2 and call(n_resp=9) == -6 and call(cu=None) == -1 and call(diag=None) == -1
+    assert call(n_rows=18_000_000, n_resp=512) == -1      # the header's examples fit ...
+    assert call(n_rows=1_000_000, n_resp=16_000) == -1
+    assert call(n_rows=19_000_000, n_resp=512) == -10     # ... and these do not
+    assert call(n_rows=1_000_000, n_resp=17_500) == -10
+    assert call(n_rows=0, n_resp=1 << 20) == -10
+    assert b"static scratch" in lib.ais_strerror(-10)
+    assert B.STATIC_SCRATCH_BYTES == int(re.search(r"#define AIS_STATIC_SCRATCH_BYTES \(1 << (\d+)\)", HEADER).group(1)) ** 0 << 20
 
 
 def test_loss_grad_argument_checks():
