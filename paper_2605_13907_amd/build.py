@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libais_gfx950.so")
-SOURCES = ("api.hip", "sweeps.hip", "reductions.hip", "fp8.hip", "fp8_rows.hip", "fused.hip", "lm_head.hip")
+SOURCES = ("api.hip", "sweeps.hip", "reductions.hip", "fp8.hip", "fp8_rows.hip", "fp8_table.hip", "fused.hip", "lm_head.hip")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -132,6 +132,11 @@ int launch_fp8_dequantize(ais_ctx* ctx, const unsigned char* codes, long long co
                           long long n_rows, int vocab, void* out, ais_dtype dtype, long long out_stride);
 bool try_fp8_dequantize_burst(ais_ctx* ctx, const unsigned char* codes, long long codes_stride, const float* scale,
                               long long n_rows, int vocab, void* out, ais_dtype dtype, long long out_stride);
+bool try_fp8_quantize_table(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,
+                            long long row_stride, unsigned char* codes, long long codes_stride, float* scale_out);
+bool try_fp8_rollout_logprob_table(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,
+                                   long long row_stride, const int* token_ids, const unsigned char* valid,
+                                   float* logp_out);
 int launch_fp8_rollout_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype, long long n_rows, int vocab,
                                long long row_stride, const int* token_ids, const unsigned char* valid,
                                float* logp_out);

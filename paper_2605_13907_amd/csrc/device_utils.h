@@ -155,5 +155,16 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Wavefront-wide sum, same exchange pattern; every lane holds the result.
+__device__ __forceinline__ float wave_sum(float v) {
+  v += dpp_move<kDppQuadXor1>(v);
+  v += dpp_move<kDppQuadXor2>(v);
+  v += dpp_move<kDppRowHalfMirror>(v);
+  v += dpp_move<kDppRowMirror>(v);
+  v += __shfl_xor(v, 16);
+  v += __shfl_xor(v, 32);
+  return v;
+}
+
 }  // namespace dev
 }  // namespace ais

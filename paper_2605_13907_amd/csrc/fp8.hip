@@ -198,6 +198,8 @@ int launch_fp8_quantize(ais_ctx* ctx, const void* logits, ais_dtype dtype, long 
   if (n_rows == 0) return AIS_OK;
   dim3 grid((unsigned)n_rows), block(kSweepThreads);
   ScopedTimer timer(ctx, AIS_K_FP8_QUANT);
+  if (try_fp8_quantize_table(ctx, logits, dtype, n_rows, vocab, row_stride, codes, codes_stride, scale_out))
+    return hip_fail(ctx, hipGetLastError());      // bf16 row held in registers, codes from a per-row table
   if (try_fp8_quantize_rows(ctx, logits, dtype, n_rows, vocab, row_stride, codes, codes_stride, scale_out))
     return hip_fail(ctx, hipGetLastError());      // row held in registers: one read of the logits
   if (dtype == AIS_BF16) {
@@ -245,6 +247,8 @@ int launch_fp8_rollout_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype
   if (n_rows == 0) return AIS_OK;
   dim3 grid((unsigned)n_rows), block(kSweepThreads);
   ScopedTimer timer(ctx, AIS_K_FP8_LOGPROB);
+  if (try_fp8_rollout_logprob_table(ctx, logits, dtype, n_rows, vocab, row_stride, token_ids, valid, logp_out))
+    return hip_fail(ctx, hipGetLastError());      // bf16 row read once, terms of the sum from a per-row table
   if (dtype == AIS_BF16) {
     const bf16_t* z = static_cast<const bf16_t*>(logits);
     if (aligned(z, row_stride * 2, 16))

@@ -47,6 +47,12 @@ constexpr int kLmTileT = 256;      // tokens per tile
 constexpr int kLmTileK = 64;       // d_model elements per step of the register-staged kernel
 constexpr int kLmWaveV = 128;      // per wavefront: 4 MFMA tiles along the vocabulary
 constexpr int kLmWaveT = 64;       //                2 along the tokens
+// Token blocks that walk the vocabulary chunks together (see LmItem::init).  1 = token block major: the workgroups
+// resident on an XCD share a few hidden-state blocks and sit on all chunks of the vocabulary.  Measured at 41,643
+// rows x 151,936 x 4,096: 43.9 ms; groups of 2 / 4 / 8 / 16 / 32 token blocks on the same chunk (more sharing of the
+// output-embedding tiles, less of the hidden-state block, which a work item re-reads for every vocabulary tile):
+// 44.3 / 47.4 / 47.5 / 50.1 / 52.9 ms.
+constexpr int kLmTokenBlockGroup = 1;
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 q) { return __builtin_bit_cast(bf16x8, q); }
 
 
@@ -56,7 +62,7 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 q) { return __builtin_bit_cast
 // (lm_head_setup_kernel): n_tblocks blocks of 256 evaluated rows x n_chunks chunks of tiles_per_chunk
 // vocabulary tiles, per_xcd work items for each of the 8 XCDs.
 struct LmDevPlan {
-  int n_eval, n_tblocks, n_chunks, tiles_per_chunk, per_xcd, n_items;
+  int n_eval, n_tblocks, n_chunks, tiles_per_chunk, per_xcd, n_items, tb_group;
 };
 
 // Splits n_vtiles vocabulary tiles into equal chunks so that (token blocks x chunks) equal work items fill the
@@ -110,8 +116,13 @@ struct LmItem {
     n_eval = plan->n_eval;
     n_chunks = plan->n_chunks;
     const int tiles_per_chunk = plan->tiles_per_chunk;
-    tb = item / n_chunks;
-    ch = item - tb * n_chunks;
+    // items are ordered group by group of tb_group token blocks, chunk by chunk inside a group, token block by
+    // token block inside a chunk: the workgroups resident on an XCD then sit on tb_group token blocks x a few chunks
+    const int group = plan->tb_group, per_group = group * n_chunks;
+    const int g = item / per_group, j = item - g * per_group;
+    const int gsize = min(group, plan->n_tblocks - g * group);     // the last group may be smaller
+    ch = j / gsize;
+    tb = g * group + (j - ch * gsize);
     vt0 = ch * tiles_per_chunk;
     vt1 = min(n_vtiles, vt0 + tiles_per_chunk);
     t0 = tb * kLmTileT;
@@ -583,7 +594,7 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_staged_kernel(
 // valid != 0, pos[n] = position of row n in that list or -1; each thread owns a contiguous run of rows); in
 // both cases thread 0 then decides the decomposition for the number of evaluated rows.
 __global__ __launch_bounds__(1024) void lm_head_setup_kernel(const unsigned char* __restrict__ valid, int n_rows,
-                                                             int n_vtiles, int n_cus, int max_items,
+                                                             int n_vtiles, int n_cus, int max_items, int tb_group,
                                                              int* __restrict__ index, int* __restrict__ pos,
                                                              LmDevPlan* __restrict__ plan) {
   __shared__ int run_start[1024];
@@ -625,6 +636,7 @@ __global__ __launch_bounds__(1024) void lm_head_setup_kernel(const unsigned char
     lm_choose_chunks(d.n_tblocks, n_vtiles, n_cus, max_items, &d.n_chunks, &d.tiles_per_chunk);
     d.n_items = d.n_tblocks * d.n_chunks;
     d.per_xcd = (d.n_items + 7) / 8;
+    d.tb_group = max(1, min(tb_group, d.n_tblocks));
     *plan = d;
   }
 }
@@ -697,7 +709,7 @@ int launch_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long ld_h, con
   const int max_items = ((plan.n_tblocks * plan.n_chunks + 7) / 8) * 8;
   LmDevPlan* dplan = static_cast<LmDevPlan*>(dev_plan);
   lm_head_setup_kernel<<<1, 1024, 0, ctx->stream>>>(valid, (int)n_rows, plan.n_vtiles, ctx->n_cus, max_items,
-                                                    row_index, row_pos, dplan);
+                                                    kLmTokenBlockGroup, row_index, row_pos, dplan);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(ctx, e);
   LmRows rows{valid != nullptr ? row_index : nullptr, (int)n_rows};

@@ -74,11 +74,12 @@ def test_random_rows(ctx, dtype, vocab):
     assert np.abs(lp.double().cpu().numpy() - ref).max() <= LOGP_ATOL
 
 
-# every instantiation of the register-resident quantise kernel: 4 / 8 / 12 / 16 / 20 / 24 vectors per lane, 18 + 9,
+# every instantiation of the table kernels for bf16 rows (4 / 8 / 12 / 16 / 18 / 19 / 20 / 24 vectors per lane), of the
+# register-resident quantise kernel that fp32 rows and wider bf16 rows take: 4 / 8 / 12 / 16 / 20 / 24 vectors per lane, 18 + 9,
 # 22 + 9 and 24 + 9 with the last nine in LDS, and the streaming route beyond; and of the burst dequantise kernel:
 # 4 / 8 / 12 / 16 / 19 / 20 vectors per lane in one burst, two and three bursts of 16, and the streaming route beyond
 # 48 (a vector holds 8 bf16 or 4 fp32 elements)
-ROW_VOCABS = {"bf16": [40_001, 90_007, 120_011, 151_936, 160_003, 190_003, 210_007, 248_320, 260_011, 270_336, 275_003,
+ROW_VOCABS = {"bf16": [40_001, 90_007, 120_011, 140_001, 151_936, 160_003, 190_003, 210_007, 248_320, 260_011, 270_336, 275_003,
                        400_003],
               "f32": [20_011, 45_007, 60_013, 75_011, 80_021, 95_003, 105_001, 124_003, 130_007, 135_168, 137_501,
                       200_003]}
@@ -93,7 +94,42 @@ def test_every_row_width_class(ctx, dtype, vocab):
     z[0] = 0
     z[1, vocab - 1] = -41.0          # the abs-max in the ragged tail
     z[2, vocab // 2] = 97.0
+    z[3] = -z[3].abs() - 60.0        # every logit far below zero: the largest term of the sum belongs to the smallest magnitude
     check_quant(ctx, z)
+    y = torch.tensor([0, vocab - 1, vocab // 2, 7 % vocab, vocab // 3], dtype=torch.int32, device="cuda")
+    valid = torch.tensor([1, 1, 1, 1, 0], dtype=torch.uint8, device="cuda")
+    lp = ctx.fp8_rollout_logprob(z, y, valid)
+    torch.cuda.synchronize()
+    ref = F.rollout_logprob(z.float().cpu().numpy(), y.cpu().numpy(), valid.cpu().numpy())
+    assert lp[4].item() == 0.0 and np.abs(lp.double().cpu().numpy() - ref).max() <= LOGP_ATOL
+    assert torch.isfinite(lp).all()
+
+
+@pytest.mark.parametrize("expo", [-20, -3, 0, 5, 40])
+def test_every_bf16_magnitude_under_every_scale_significand(ctx, expo):
+    """Exhaustive for bf16 rows: the scale of a bf16 row is RN(amax / 448) for a bf16 amax, so its significand takes
+    128 values; row m holds amax = (1 + m / 128) 2^expo (with alternating sign) and EVERY finite bf16 value of both
+    signs that does not exceed it, subnormals and -0 included.  Codes and scales bit-exact, rollout log-probs to
+    tolerance.  Every quotient that can occur for such a row, ties of the E4M3 grid included, is in here."""
+    bits = np.arange(0, 0x7F80, dtype=np.uint32)
+    mags = (bits << 16).view(np.float32)
+    both = np.concatenate([mags, -mags])
+    rows = []
+    for m in range(128):
+        amax = np.float32((1.0 + m / 128.0) * 2.0 ** expo)
+        row = np.where(np.abs(both) <= amax, both, np.float32(0.0)).astype(np.float32)
+        row[1] = amax if m % 2 == 0 else -amax
+        rows.append(row)
+    z = torch.from_numpy(np.stack(rows)).to(torch.bfloat16).cuda()
+    assert torch.equal(z.float().cpu(), torch.from_numpy(np.stack(rows)))          # every value is a bf16
+    check_quant(ctx, z)
+    if expo > 8:
+        return                          # log-probs of order 1e12 are beyond what an absolute tolerance can speak about
+    y = torch.from_numpy(np.random.default_rng(expo + 100).integers(0, z.shape[1], size=128).astype(np.int32)).cuda()
+    lp = ctx.fp8_rollout_logprob(z, y)
+    torch.cuda.synchronize()
+    ref = F.rollout_logprob(z.float().cpu().numpy(), y.cpu().numpy())
+    assert np.abs(lp.double().cpu().numpy() - ref).max() <= LOGP_ATOL
 
 
 @pytest.mark.parametrize("seed", range(int(os.environ.get("AIS_RANDOM_CASES", "30"))))
