@@ -337,7 +337,42 @@ def main():
             "library_gemm_yardstick": {"avg_ms": ms_gemm, "TFLOP/s": flops / (ms_gemm * 1e-3) / 1e12,
                                        "note": "torch.matmul to bf16 logits; the materialised route adds the "
                                                "token_logprob sweep above to this"}}
-        del z, rb
+        # gradient w.r.t. hidden states and output embedding without materialised logits (recompute on the matrix
+        # cores, chunk by chunk, + two library GEMMs per chunk), against the route that materialises the logits
+        # (library GEMM, the two sweeps of this library, two library GEMMs on the [R, V] dlogits)
+        logp_h, lse_h = ctx.lm_head_logprob(rb.hidden, rb.weight, rb.token_ids, rb.valid, p.inv_temperature)
+        gen_c = torch.Generator(device="cuda").manual_seed(23)
+        coeff = torch.randn(R, device="cuda", generator=gen_c) * 1e-5 * (rb.valid != 0)
+        ctx.lm_head_grad(rb.hidden, rb.weight, rb.token_ids, lse_h, logp_h, coeff, p.inv_temperature)
+        ctx.profile(True)
+        ev0.record()
+        for _ in range(3):
+            dh, dw = ctx.lm_head_grad(rb.hidden, rb.weight, rb.token_ids, lse_h, logp_h, coeff, p.inv_temperature)
+        ev1.record()
+        torch.cuda.synchronize()
+        ms_grad = ev0.elapsed_time(ev1) / 3
+        ms_rec, n_rec = ctx.profile_read(binding.AIS_K_LM_HEAD_GRAD)
+        ctx.profile(False)
+        del dh, dw
+        dh16 = torch.empty(R, Dm, dtype=torch.bfloat16, device="cuda")
+        dw16 = torch.empty(V, Dm, dtype=torch.bfloat16, device="cuda")
+        for it in range(4):
+            if it == 1:
+                ev0.record()
+            torch.matmul(z, rb.weight, out=dh16)              # dhidden = dlogits W      (z stands in for dlogits)
+            torch.matmul(z.t(), rb.hidden, out=dw16)          # dweight = dlogits^T H
+        ev1.record()
+        torch.cuda.synchronize()
+        ms_two = ev0.elapsed_time(ev1) / 3
+        k_fwd, k_bwd = result["kernels"]["token_logprob"]["avg_ms"], result["kernels"]["dlogits"]["avg_ms"]
+        extras["lm_head_grad"] = {
+            "avg_ms": ms_grad, "recompute_kernel_ms": ms_rec / 3, "chunks": n_rec // 3, "flops": 3 * flops,
+            "TFLOP/s": 3 * flops / (ms_grad * 1e-3) / 1e12, "frac_of_mfma_peak": 3 * flops / (ms_grad * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "dlogits_bytes_held": 2 * R * 8192, "logits_bytes_of_materialised_route": 2 * R * V,
+            "materialised_route": {"ms": ms_gemm + k_fwd + k_bwd + ms_two, "logits_gemm_ms": ms_gemm,
+                                   "two_sweeps_ms": k_fwd + k_bwd, "two_gradient_gemms_ms": ms_two,
+                                   "note": "library GEMMs with bf16 outputs; the sweeps are this library's"}}
+        del z, rb, dh16, dw16
         result["next_rows"] = extras
     if args.cpu_rows > 0:
         params = dict(C=p.C, delta=p.delta, gamma=p.gamma, eps_std=p.eps_std, beta_var=p.beta_var,

@@ -303,12 +303,37 @@ int ais_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long hidden_strid
                         long long vocab, const int* token_ids, const unsigned char* valid,
                         float inv_temperature, float* logp_out, float* lse_out);
 
+/* Gradient of the loss with respect to the last hidden states and the output-embedding matrix, again without
+ * materialised logits (Alg. 1, "Policy Update": the gradient of Eq. 19 reaches the model through the read-out).
+ * With z = hidden weight^T, p = softmax(inv_temperature z) and the per-row coefficient c (zero where a row has
+ * no gradient: not evaluated, zero advantage, clipped away):
+ *   dlogits[n, v]  = c[n] (p[n, v] - 1[v = y_n])                      (never stored as a whole)
+ *   dhidden[n, :]  = sum_v dlogits[n, v] weight[v, :]
+ *   dweight[v, :]  = sum_n dlogits[n, v] hidden[n, :]
+ * The vocabulary is walked in chunks: the logits of a chunk are recomputed on the matrix cores from the operands,
+ * turned into dlogits (bf16) with the row's lse, and consumed at once by two library GEMMs (rocBLAS, fp32
+ * accumulation and output); only [n_rows, chunk_vocab] dlogits exist at any time.
+ *   hidden, weight, token_ids, dtype, strides   as for ais_lm_head_logprob; d_model a multiple of 32
+ *   lse, logp   [n_rows] fp32, outputs of ais_lm_head_logprob for the same operands and temperature
+ *   coeff       [n_rows] fp32, as written by ais_grpo_row_scale (its g_out: it carries inv_temperature)
+ *   chunk_vocab vocabulary entries per chunk, a multiple of 256; 0 selects 8192.  The context workspace grows to
+ *               2 * n_rows * chunk_vocab bytes.
+ *   dhidden_out [n_rows, d_model] fp32, contiguous; dweight_out [vocab, d_model] fp32, contiguous; both are
+ *               overwritten.
+ * Errors: as ais_lm_head_logprob; d_model not a multiple of 32 or chunk_vocab not a multiple of 256
+ * (AIS_ERR_SIZE); a failing library call (AIS_ERR_HIP). */
+int ais_lm_head_grad(ais_ctx* ctx, const void* hidden, long long hidden_stride, const void* weight,
+                     long long weight_stride, ais_dtype dtype, long long n_rows, long long d_model,
+                     long long vocab, const int* token_ids, const float* lse, const float* logp,
+                     const float* coeff, float inv_temperature, long long chunk_vocab, float* dhidden_out,
+                     float* dweight_out);
+
 /* ---- measurement helpers -------------------------------------------------------------------- */
 
 /* Kernels whose device time can be read back. */
 typedef enum ais_kernel {
   AIS_K_LOGPROB = 0, AIS_K_DLOGITS = 1, AIS_K_COPY = 2, AIS_K_FP8_QUANT = 3, AIS_K_FP8_DEQUANT = 4,
-  AIS_K_FP8_LOGPROB = 5, AIS_K_FUSED = 6, AIS_K_LM_HEAD = 7, AIS_K_COUNT_ = 8
+  AIS_K_FP8_LOGPROB = 5, AIS_K_FUSED = 6, AIS_K_LM_HEAD = 7, AIS_K_LM_HEAD_GRAD = 8, AIS_K_COUNT_ = 9
 } ais_kernel;
 
 /* With `enable` != 0 every launch of the kernels above is bracketed by HIP events on the

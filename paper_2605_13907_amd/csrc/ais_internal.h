@@ -77,6 +77,7 @@ struct ais_ctx {
     bool valid = false;
   } plan;
   void* static_scratch = nullptr;   // address, on this context's device, of the library's static scratch array
+  void* blas = nullptr;             // rocblas_handle of the two plain GEMMs of ais_lm_head_grad, created on first use
 };
 
 namespace ais {
@@ -141,6 +142,10 @@ int launch_fp8_rollout_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype
                                long long row_stride, const int* token_ids, const unsigned char* valid,
                                float* logp_out);
 
+int launch_lm_head_dlogits_chunk(ais_ctx* ctx, const void* hidden, long long ld_h, const void* weight,
+                                 long long ld_w, long long n_rows, int d_model, int vocab, int y_off,
+                                 const int* token_ids, const float* lse, const float* logp, const float* coeff,
+                                 float inv_temperature, void* dev_plan, void* ds, long long ds_stride);
 int launch_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long ld_h, const void* weight, long long ld_w,
                            long long n_rows, int d_model, int vocab, const int* token_ids,
                            const unsigned char* valid, float inv_temperature, const LmHeadPlan& plan,

@@ -1,8 +1,11 @@
 // The C entry points: host-side argument checks, workspace, launches.  See include/ais.h for the contract.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <mutex>
 #include <new>
+
+#include <rocblas/rocblas.h>
 
 #include "ais_internal.h"
 
@@ -241,6 +244,7 @@ int ais_destroy(ais_ctx* ctx) {
     (void)hipEventDestroy(t.stop);
   }
   for (auto& e : ctx->pool) (void)hipEventDestroy(e);
+  if (ctx->blas != nullptr) (void)rocblas_destroy_handle(static_cast<rocblas_handle>(ctx->blas));
   if (ctx->ws != nullptr) (void)hipFree(ctx->ws);
   if (ctx->status_dev != nullptr) (void)hipFree(ctx->status_dev);
   delete ctx;
@@ -490,6 +494,77 @@ int ais_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long hidden_strid
   return launch_lm_head_logprob(ctx, hidden, hidden_stride, weight, weight_stride, n_rows, (int)d_model, (int)vocab,
                                 token_ids, valid, inv_temperature, plan, part_m, part_s, zy, row_index, row_pos,
                                 dev_plan, logp_out, lse_out);
+}
+
+int ais_lm_head_grad(ais_ctx* ctx, const void* hidden, long long hidden_stride, const void* weight,
+                     long long weight_stride, ais_dtype dtype, long long n_rows, long long d_model, long long vocab,
+                     const int* token_ids, const float* lse, const float* logp, const float* coeff,
+                     float inv_temperature, long long chunk_vocab, float* dhidden_out, float* dweight_out) {
+  if (dtype != AIS_BF16) return AIS_ERR_DTYPE;
+  if (n_rows < 0 || n_rows > 0x7fffffffLL - 256) return AIS_ERR_SIZE;
+  if (vocab < 1 || vocab > 0x7fffffffLL - 256) return AIS_ERR_SIZE;
+  if (d_model < 32 || d_model > (1 << 20) || d_model % 32 != 0) return AIS_ERR_SIZE;
+  if (chunk_vocab == 0) chunk_vocab = 8192;
+  if (chunk_vocab < 256 || chunk_vocab > (1 << 24) || chunk_vocab % 256 != 0) return AIS_ERR_SIZE;
+  if (hidden_stride < d_model || weight_stride < d_model) return AIS_ERR_STRIDE;
+  if (weight == nullptr || dweight_out == nullptr) return AIS_ERR_NULL;
+  if (n_rows > 0 && (hidden == nullptr || token_ids == nullptr || lse == nullptr || logp == nullptr ||
+                     coeff == nullptr || dhidden_out == nullptr))
+    return AIS_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(hidden) % 16 != 0 || reinterpret_cast<uintptr_t>(weight) % 16 != 0 ||
+      hidden_stride % 8 != 0 || weight_stride % 8 != 0 || reinterpret_cast<uintptr_t>(dhidden_out) % 4 != 0 ||
+      reinterpret_cast<uintptr_t>(dweight_out) % 4 != 0)
+    return AIS_ERR_ALIGN;
+  if (!std::isfinite(inv_temperature) || inv_temperature <= 0.f) return AIS_ERR_PARAM;
+  if (ctx == nullptr) return AIS_ERR_NULL;
+  DeviceGuard guard(ctx->device);
+  const size_t dw_bytes = sizeof(float) * (size_t)vocab * (size_t)d_model;
+  if (n_rows == 0) return hip_fail(ctx, hipMemsetAsync(dweight_out, 0, dw_bytes, ctx->stream));
+  if (chunk_vocab > ((vocab + 255) / 256) * 256) chunk_vocab = ((vocab + 255) / 256) * 256;
+  // workspace: the chunk's dlogits, then the device-side decomposition of the recompute kernel
+  const size_t ds_bytes = ((size_t)n_rows * (size_t)chunk_vocab * 2 + 255) & ~size_t(255);
+  int rc = ensure_workspace(ctx, ds_bytes + 256);
+  if (rc != AIS_OK) return rc;
+  ctx->plan.valid = false;             // the chunk's dlogits overwrite whatever tiling the workspace held
+  char* ds = static_cast<char*>(ctx->ws);
+  void* dev_plan = ds + ds_bytes;
+  if (ctx->blas == nullptr) {
+    rocblas_handle h = nullptr;
+    if (rocblas_create_handle(&h) != rocblas_status_success) return AIS_ERR_HIP;
+    ctx->blas = h;
+  }
+  rocblas_handle blas = static_cast<rocblas_handle>(ctx->blas);
+  if (rocblas_set_stream(blas, ctx->stream) != rocblas_status_success) return AIS_ERR_HIP;
+  if (rocblas_set_pointer_mode(blas, rocblas_pointer_mode_host) != rocblas_status_success) return AIS_ERR_HIP;
+  const float one = 1.f, zero = 0.f;
+  const char* w_base = static_cast<const char*>(weight);
+  for (long long v0 = 0; v0 < vocab; v0 += chunk_vocab) {
+    const int width = (int)std::min<long long>(chunk_vocab, vocab - v0);
+    const void* w_chunk = w_base + (size_t)v0 * (size_t)weight_stride * 2;
+    rc = launch_lm_head_dlogits_chunk(ctx, hidden, hidden_stride, w_chunk, weight_stride, n_rows, (int)d_model, width,
+                                      (int)v0, token_ids, lse, logp, coeff, inv_temperature, dev_plan, ds,
+                                      chunk_vocab);
+    if (rc != AIS_OK) return rc;
+    // The library is column-major; a row-major [r, c] matrix with pitch p is its column-major [c, r] transpose
+    // with leading dimension p.
+    // dhidden[n_rows, D] (+)= ds[n_rows, width] weight_chunk[width, D]:   C^T[D, n_rows] = W_c^T[D, width] ds^T[width, n_rows]
+    rocblas_status st = rocblas_gemm_ex(
+        blas, rocblas_operation_none, rocblas_operation_none, (rocblas_int)d_model, (rocblas_int)n_rows, width, &one,
+        w_chunk, rocblas_datatype_bf16_r, (rocblas_int)weight_stride, ds, rocblas_datatype_bf16_r,
+        (rocblas_int)chunk_vocab, v0 == 0 ? &zero : &one, dhidden_out, rocblas_datatype_f32_r, (rocblas_int)d_model,
+        dhidden_out, rocblas_datatype_f32_r, (rocblas_int)d_model, rocblas_datatype_f32_r, rocblas_gemm_algo_standard,
+        0, 0);
+    if (st != rocblas_status_success) return AIS_ERR_HIP;
+    // dweight_chunk[width, D] = ds^T[width, n_rows] hidden[n_rows, D]:   C^T[D, width] = H^T[D, n_rows] ds[n_rows, width]
+    float* dw_chunk = dweight_out + (size_t)v0 * (size_t)d_model;
+    st = rocblas_gemm_ex(blas, rocblas_operation_none, rocblas_operation_transpose, (rocblas_int)d_model, width,
+                         (rocblas_int)n_rows, &one, hidden, rocblas_datatype_bf16_r, (rocblas_int)hidden_stride, ds,
+                         rocblas_datatype_bf16_r, (rocblas_int)chunk_vocab, &zero, dw_chunk, rocblas_datatype_f32_r,
+                         (rocblas_int)d_model, dw_chunk, rocblas_datatype_f32_r, (rocblas_int)d_model,
+                         rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0);
+    if (st != rocblas_status_success) return AIS_ERR_HIP;
+  }
+  return AIS_OK;
 }
 
 int ais_profile(ais_ctx* ctx, int enable) {

@@ -250,6 +250,85 @@ struct LmSoftmax {
   }
 };
 
+// What the gradient variant of the streaming kernel needs besides the operands: per-row lse, log-prob and
+// coefficient (inputs), and the block of dlogits it writes: rows x a chunk of the vocabulary, bf16, row-major.
+struct LmGradArgs {
+  const float* lse;        // [n_rows]  log sum_v exp(z / T), as written by the log-prob call
+  const float* logp;       // [n_rows]  log-prob of the sampled token
+  const float* coeff;      // [n_rows]  d loss / d (row's log-prob) times 1 / T; 0 on rows without gradient
+  bf16_t* ds;              // [n_rows, ds_stride]  coeff (softmax - onehot) over this chunk of the vocabulary
+  long long ds_stride;     // elements, a multiple of 4
+  int y_off;               // first vocabulary entry of the chunk: token ids are global, tile indices local
+};
+
+// Per-lane state of the gradient variant: for each of the lane's two token columns the row it writes to, the
+// sampled token's position inside the chunk, -lse in the base-2 domain, the coefficient and the sampled token's
+// own element coeff (p_y - 1) = coeff expm1(logp), which would cancel if it were formed from p_y.
+struct LmGrad {
+  long long row[2];
+  int y[2];
+  float shift[2], c[2], dy[2];
+  __device__ __forceinline__ void init(const LmItem& it, const LmRows& rows, int vocab,
+                                       const int* __restrict__ token_ids, const LmGradArgs& ga) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int tok = it.t0 + it.wt * kLmWaveT + j * 32 + it.col;
+      row[j] = -1;
+      y[j] = -1;
+      shift[j] = 0.f;
+      c[j] = 0.f;
+      dy[j] = 0.f;
+      if (tok < it.n_eval) {
+        const int r = rows.row(tok, it.n_eval);
+        row[j] = r;
+        c[j] = ga.coeff[r];
+        if (c[j] != 0.f) {                  // rows without gradient: lse may be 0 there, and nothing is exponentiated
+          const int id = token_ids[r] - ga.y_off;
+          y[j] = (id >= 0 && id < vocab) ? id : -1;
+          shift[j] = -ga.lse[r] * kLog2e;
+          dy[j] = c[j] * expm1f(ga.logp[r]);
+        }
+      }
+    }
+  }
+  // Writes the finished tile `vt`.  Accumulator element v of MFMA tile i holds vocabulary entry
+  // vbase + 32 i + 8 (v / 4) + 4 half + v % 4 of token column j: four consecutive entries per (i, v / 4), 8 bytes.
+  __device__ __forceinline__ void emit(const LmAcc& acc, const LmItem& it, int vt, int vocab, float scale,
+                                       const LmGradArgs& ga) {
+    const int vbase = vt * kLmTileV + it.wv * kLmWaveV;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      if (row[j] < 0) continue;
+      bf16_t* out = ga.ds + row[j] * ga.ds_stride;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int v0 = vbase + 32 * i + 8 * q + 4 * it.half;
+          if (v0 >= vocab) continue;
+          float x[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            x[e] = c[j] != 0.f ? c[j] * exp2_fast(fmaf(acc[i][j][4 * q + e], scale, shift[j])) : 0.f;
+            if (v0 + e == y[j]) x[e] = dy[j];
+          }
+          if (v0 + 3 < vocab) {
+            f32x2 lo = {x[0], x[1]}, hi = {x[2], x[3]};
+            uint2 w = {__builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2)),
+                       __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2))};
+            *reinterpret_cast<uint2*>(out + v0) = w;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (v0 + e < vocab) Vec<bf16_t>::store1(out + v0 + e, x[e]);
+          }
+        }
+    }
+    // the kernel counts its outstanding global->LDS copies; these stores must not be among them
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+};
+
 typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef const __attribute__((address_space(1))) void* glb_ptr;
 
@@ -271,12 +350,14 @@ constexpr int kStStageBytes = 2 * kStOperandBytes;               // 32 KiB
 // consecutive rows, read at one logical chunk, cover all 16 bank groups.
 __device__ __forceinline__ int st_chunk_offset(int row, int c) { return row * 64 + ((c ^ ((row >> 2) & 3)) << 4); }
 
-template <int NS>
+// GRAD = false: every finished tile is folded into the running soft-max state (log-prob call).  GRAD = true: every
+// finished tile is written out as coeff (softmax - onehot) in bf16, lse being an input (gradient call).
+template <int NS, bool GRAD>
 __global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(
     const bf16_t* __restrict__ hidden, long long ld_h, const bf16_t* __restrict__ weight, long long ld_w,
     LmRows rows, const LmDevPlan* __restrict__ plan, int d_model, int vocab, const int* __restrict__ token_ids,
     float scale, int n_vtiles, float* __restrict__ part_m, float* __restrict__ part_s,
-    float* __restrict__ zy_out) {
+    float* __restrict__ zy_out, LmGradArgs ga) {
   extern __shared__ __align__(16) unsigned char lds[];
   LmItem it;
   if (!it.init(plan, n_vtiles)) return;
@@ -363,7 +444,13 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
   };
   LmSoftmax sm;
-  sm.init(it, rows, vocab, token_ids);
+  LmGrad gr;
+  if (GRAD) gr.init(it, rows, vocab, token_ids, ga);
+  else sm.init(it, rows, vocab, token_ids);
+  auto tile_done = [&](int tile) {
+    if (GRAD) gr.emit(acc, it, tile, vocab, scale, ga);
+    else sm.fold(acc, it, tile, vocab, scale, zy_out);
+  };
 
   // Every wavefront issues 4 copies per step and they complete in order: waiting until at most 4 * younger
   // are outstanding means the step before the `younger` most recent ones has landed.
@@ -433,7 +520,7 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(
       AIS_PIN;
     }
     if (++kt == n_ksteps) {
-      sm.fold(acc, it, vt, vocab, scale, zy_out);
+      tile_done(vt);
       lm_clear(acc);
       kt = 0;
       ++vt;
@@ -442,10 +529,10 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(
   }
 #undef AIS_PIN
   mfma_range(a1, b1, 2, 8);
-  sm.fold(acc, it, vt, vocab, scale, zy_out);
+  tile_done(vt);
   // copies of the last steps may still be in flight, and they land in LDS that finish() is about to reuse
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  sm.finish(it, reinterpret_cast<float*>(lds), n_rows, part_m, part_s);
+  if (!GRAD) sm.finish(it, reinterpret_cast<float*>(lds), n_rows, part_m, part_s);
 }
 
 // ---- register-staged kernel: any d_model that is a multiple of 8 ---------------------------------------------
@@ -699,7 +786,7 @@ int launch_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long ld_h, con
   constexpr int kStreamLds = AIS_LM_STAGES * kStStageBytes;
   static std::once_flag once_stream[kMaxDevices], once_staged[kMaxDevices];   // per function and device
   static bool ok_stream[kMaxDevices], ok_staged[kMaxDevices];
-  if (!allow_dynamic_lds(ctx, reinterpret_cast<const void*>(lm_head_stream_kernel<AIS_LM_STAGES>), kStreamLds,
+  if (!allow_dynamic_lds(ctx, reinterpret_cast<const void*>(lm_head_stream_kernel<AIS_LM_STAGES, false>), kStreamLds,
                          once_stream, ok_stream) ||
       !allow_dynamic_lds(ctx, reinterpret_cast<const void*>(lm_head_staged_kernel), kLmLdsBytes, once_staged,
                          ok_staged))
@@ -715,17 +802,51 @@ int launch_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long ld_h, con
   LmRows rows{valid != nullptr ? row_index : nullptr, (int)n_rows};
   {
     ScopedTimer timer(ctx, AIS_K_LM_HEAD);
-    const bool stream = d_model % kStK == 0;
-    auto kernel = stream ? lm_head_stream_kernel<AIS_LM_STAGES> : lm_head_staged_kernel;
-    kernel<<<max_items, kLmThreads, stream ? kStreamLds : kLmLdsBytes, ctx->stream>>>(
-        static_cast<const bf16_t*>(hidden), ld_h, static_cast<const bf16_t*>(weight), ld_w, rows, dplan, d_model,
-        vocab, token_ids, inv_temperature * kLog2e, plan.n_vtiles, part_m, part_s, zy);
+    if (d_model % kStK == 0)
+      lm_head_stream_kernel<AIS_LM_STAGES, false><<<max_items, kLmThreads, kStreamLds, ctx->stream>>>(
+          static_cast<const bf16_t*>(hidden), ld_h, static_cast<const bf16_t*>(weight), ld_w, rows, dplan, d_model,
+          vocab, token_ids, inv_temperature * kLog2e, plan.n_vtiles, part_m, part_s, zy, LmGradArgs{});
+    else
+      lm_head_staged_kernel<<<max_items, kLmThreads, kLmLdsBytes, ctx->stream>>>(
+          static_cast<const bf16_t*>(hidden), ld_h, static_cast<const bf16_t*>(weight), ld_w, rows, dplan, d_model,
+          vocab, token_ids, inv_temperature * kLog2e, plan.n_vtiles, part_m, part_s, zy);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(ctx, e);
   lm_head_merge_kernel<<<(unsigned)((n_rows + 255) / 256), 256, 0, ctx->stream>>>(
       part_m, part_s, zy, (int)n_rows, dplan, vocab, token_ids, valid != nullptr ? row_pos : nullptr,
       inv_temperature, logp_out, lse_out, ctx->status_dev);
+  return hip_fail(ctx, hipGetLastError());
+}
+
+// dlogits of one chunk of the vocabulary, from hidden states and the chunk's rows of the output embedding, into
+// ds[n_rows, ds_stride] (bf16).  `weight` points at the chunk's first row, `vocab` is the chunk's width, `y_off` its
+// first vocabulary entry.  Every row is processed (rows whose coefficient is 0 come out as zeros).
+int launch_lm_head_dlogits_chunk(ais_ctx* ctx, const void* hidden, long long ld_h, const void* weight,
+                                 long long ld_w, long long n_rows, int d_model, int vocab, int y_off,
+                                 const int* token_ids, const float* lse, const float* logp, const float* coeff,
+                                 float inv_temperature, void* dev_plan, void* ds, long long ds_stride) {
+  constexpr int kStreamLds = AIS_LM_STAGES * kStStageBytes;
+  static std::once_flag once[kMaxDevices];
+  static bool ok[kMaxDevices];
+  if (!allow_dynamic_lds(ctx, reinterpret_cast<const void*>(lm_head_stream_kernel<AIS_LM_STAGES, true>), kStreamLds,
+                         once, ok))
+    return hip_fail(ctx, hipErrorInvalidValue);
+  const LmHeadPlan plan = lm_head_plan(n_rows, vocab, ctx->n_cus);
+  const int max_items = ((plan.n_tblocks * plan.n_chunks + 7) / 8) * 8;
+  LmDevPlan* dplan = static_cast<LmDevPlan*>(dev_plan);
+  lm_head_setup_kernel<<<1, 1024, 0, ctx->stream>>>(nullptr, (int)n_rows, plan.n_vtiles, ctx->n_cus, max_items,
+                                                    kLmTokenBlockGroup, nullptr, nullptr, dplan);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  LmRows rows{nullptr, (int)n_rows};
+  LmGradArgs ga{lse, logp, coeff, static_cast<bf16_t*>(ds), ds_stride, y_off};
+  {
+    ScopedTimer timer(ctx, AIS_K_LM_HEAD_GRAD);
+    lm_head_stream_kernel<AIS_LM_STAGES, true><<<max_items, kLmThreads, kStreamLds, ctx->stream>>>(
+        static_cast<const bf16_t*>(hidden), ld_h, static_cast<const bf16_t*>(weight), ld_w, rows, dplan, d_model,
+        vocab, token_ids, inv_temperature * kLog2e, plan.n_vtiles, nullptr, nullptr, nullptr, ga);
+  }
   return hip_fail(ctx, hipGetLastError());
 }
 

@@ -318,6 +318,28 @@ def test_bench_refuses_more_than_one_gpu():
     assert not r.stdout.strip().startswith("{")              # no result line for a run that did not happen
 
 
+def test_lm_head_grad_argument_checks():
+    lib = B._lib()
+
+    def call(**kw):
+        a = dict(ctx=None, hidden=FAKE, ld_h=64, weight=FAKE, ld_w=64, dtype=B.AIS_BF16, n_rows=4, d=64, vocab=100,
+                 tok=FAKE, lse=FAKE, logp=FAKE, coeff=FAKE, inv_t=1.0, chunk=0, dh=FAKE, dw=FAKE)
+        a.update(kw)
+        return lib.ais_lm_head_grad(a["ctx"], a["hidden"], a["ld_h"], a["weight"], a["ld_w"], a["dtype"], a["n_rows"],
+                                    a["d"], a["vocab"], a["tok"], a["lse"], a["logp"], a["coeff"], a["inv_t"],
+                                    a["chunk"], a["dh"], a["dw"])
+
+    assert call() == -1                                   # everything fine except the NULL context
+    assert call(dtype=B.AIS_F32) == -7
+    assert call(d=40) == -2 and call(d=16) == -2          # the gradient call needs d_model % 32 == 0
+    assert call(chunk=100) == -2 and call(chunk=255) == -2 and call(chunk=512) == -1
+    assert call(vocab=0) == -2 and call(n_rows=-1) == -2
+    assert call(ld_h=32) == -3 and call(ld_w=60) == -3
+    assert call(weight=None) == -1 and call(dw=None) == -1 and call(lse=None) == -1 and call(coeff=None) == -1
+    assert call(hidden=C.c_void_p(0x1008)) == -4 and call(ld_w=68) == -4
+    assert call(inv_t=0.0) == -5 and call(inv_t=float("inf")) == -5
+
+
 def test_binding_rejects_host_tensors_before_any_launch():
     """A host (or foreign-device) tensor handed to a kernel would be a GPU memory fault, not an error code: the
     binding must refuse every large buffer that is not on the context's GPU before it allocates or launches
@@ -347,6 +369,8 @@ def test_binding_rejects_host_tensors_before_any_launch():
         ctx.fp8_dequantize_rows(torch.zeros(4, 64, dtype=torch.uint8), f)
     with pytest.raises(ValueError, match="hidden is on cpu"):
         ctx.lm_head_logprob(z, torch.zeros(100, 64, dtype=torch.bfloat16), tok)
+    with pytest.raises(ValueError, match="hidden is on cpu"):
+        ctx.lm_head_grad(z, torch.zeros(100, 64, dtype=torch.bfloat16), tok, f, f, f)
     with pytest.raises(ValueError, match="dst is on cpu"):
         ctx.copy(torch.zeros(16), torch.zeros(16))
     with pytest.raises(ValueError):                         # the geometry helper itself, with and without a device

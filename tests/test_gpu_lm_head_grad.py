@@ -1,0 +1,214 @@
+"""GPU parity of ais_lm_head_grad (gradient w.r.t. hidden states and the output embedding without materialised
+logits) against oracle/lm_head_oracle.grads on the same seeded bits.
+
+Tolerance, derived from the bar of the gradient w.r.t. the logits: the library forms dlogits in bf16, for which the
+stated bound is tol_dz = 1e-2 |ref| + 1e-2 * 2^-8 * max_v |ref[n, :]|; dhidden and dweight are linear in dlogits,
+
+    dhidden = dlogits W,   dweight = dlogits^T H,
+
+so an admissible dlogits can move them by at most  tol_dz |W|  resp.  tol_dz^T |H|  (element-wise absolute values),
+which is the bound used here (the fp32 accumulation of the two GEMMs adds about 1e-6 of the same sums and is covered
+by it).  The observed errors are far smaller, because the bf16 roundings of dlogits are independent: each test prints
+the worst ratio."""
+import numpy as np
+import pytest
+import torch
+
+import oracle.lm_head_oracle as L
+from paper_2605_13907_amd import binding as B
+from paper_2605_13907_amd import workloads as W
+from tests.test_gpu_lm_head import f64, make
+from tests.tolerances import dz_tolerance
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = B.AisContext()
+    yield c
+    c.close()
+
+
+def check(ctx, R, D, V, seed, p_valid=1.0, inv_t=1.0, chunk=0, scale=1.0, zero_share=0.2):
+    hidden, weight, y, valid = make(R, D, V, seed=seed, p_valid=p_valid, scale=scale)
+    rng = np.random.default_rng(seed)
+    v_np = np.ones(R, bool) if valid is None else valid.cpu().numpy().astype(bool)
+    g = rng.normal(0, 1.0, size=R) * 10.0 ** rng.uniform(-4, 0, size=R)       # coefficients of very different sizes
+    g[rng.random(R) < zero_share] = 0.0                                     # zero advantage, clipped away
+    g[~v_np] = 0.0
+    g = g.astype(np.float32)
+    logp, lse = ctx.lm_head_logprob(hidden, weight, y, valid, inv_t)
+    coeff = torch.from_numpy(g * np.float32(inv_t)).cuda()                   # what ais_grpo_row_scale hands over
+    dh, dw = ctx.lm_head_grad(hidden, weight, y, lse, logp, coeff, inv_t, chunk)
+    torch.cuda.synchronize()
+    assert ctx.status() == 0
+    h64, w64 = f64(hidden), f64(weight)
+    y_np = y.cpu().numpy()
+    live = v_np & (g != 0)
+    dz = L.dlogits(h64, w64, y_np, (coeff.cpu().numpy().astype(np.float64) / inv_t), live, inv_t)
+    ref_dh, ref_dw = dz @ w64, dz.T @ h64
+    tol_dz = dz_tolerance(dz, None, None, True)
+    tol_dh, tol_dw = tol_dz @ np.abs(w64), tol_dz.T @ np.abs(h64)
+    got_dh, got_dw = f64(dh), f64(dw)
+    assert np.all(got_dh[~live] == 0), "rows without gradient must have a zero hidden-state gradient"
+    err_h, err_w = np.abs(got_dh - ref_dh), np.abs(got_dw - ref_dw)
+    worst_h = float((err_h / np.maximum(tol_dh, 1e-300))[live].max()) if live.any() else 0.0
+    worst_w = float((err_w / np.maximum(tol_dw, 1e-300)).max()) if live.any() else 0.0
+    print(f"R={R} D={D} V={V} chunk={chunk}: worst error / bound dhidden {worst_h:.3f} dweight {worst_w:.3f}; "
+          f"max |dhidden| {np.abs(ref_dh).max():.3e} max |dweight| {np.abs(ref_dw).max():.3e}", flush=True)
+    assert np.all(err_h <= tol_dh + 1e-30) and np.all(err_w <= tol_dw + 1e-30)
+    assert worst_h < 0.5 and worst_w < 0.5                  # independent roundings: far inside the worst-case bound
+    if live.any():
+        assert np.abs(got_dh).max() > 0 and np.abs(got_dw).max() > 0
+    # the whole-path gradient also matches the oracle's own chain rule
+    oh, ow = L.grads(h64, w64, y_np, coeff.cpu().numpy().astype(np.float64) / inv_t, live, inv_t)
+    assert np.allclose(oh, ref_dh, rtol=1e-12, atol=1e-300) and np.allclose(ow, ref_dw, rtol=1e-12, atol=1e-300)
+    return dh, dw
+
+
+# rows and vocabulary ragged against the 256 x 256 tiles, one and several vocabulary chunks (chunk = 0 selects 8,192:
+# 9,000 entries are then 8,192 + 808), the smallest and a wide model width
+@pytest.mark.parametrize("R,D,V,chunk", [(1, 32, 1, 0), (5, 32, 100, 0), (256, 64, 256, 256), (257, 64, 257, 256),
+                                         (300, 96, 1000, 512), (513, 128, 2049, 1024), (640, 512, 5000, 2048),
+                                         (700, 64, 9000, 0), (300, 4096, 1500, 512), (1000, 160, 700, 256)])
+def test_shapes(ctx, R, D, V, chunk):
+    check(ctx, R, D, V, seed=R + 3 * D + V, p_valid=0.8 if R > 5 else 1.0, chunk=chunk)
+
+
+@pytest.mark.parametrize("inv_t", [0.5, 1.7])
+def test_temperature(ctx, inv_t):
+    check(ctx, 400, 256, 3000, seed=21, p_valid=0.9, inv_t=inv_t, chunk=1024, scale=3.0)
+
+
+def test_rows_without_gradient_and_determinism(ctx):
+    """All coefficients zero: both gradients are exactly zero, also on rows whose lse is 0 (not evaluated) and whose
+    token id is -1.  And two runs of the same inputs give the same bits."""
+    hidden, weight, y, valid = make(300, 64, 1000, seed=5, p_valid=0.5)
+    logp, lse = ctx.lm_head_logprob(hidden, weight, y, valid)
+    y = torch.where(valid.bool(), y, torch.full_like(y, -1))
+    zero = torch.zeros(300, device="cuda")
+    dh, dw = ctx.lm_head_grad(hidden, weight, y, lse, logp, zero, 1.0, 256)
+    assert not bool(dh.any()) and not bool(dw.any())
+    coeff = torch.where(valid.bool(), torch.full_like(zero, 0.01), zero)
+    a = ctx.lm_head_grad(hidden, weight, y, lse, logp, coeff, 1.0, 256)
+    b = ctx.lm_head_grad(hidden, weight, y, lse, logp, coeff, 1.0, 256)
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]) and torch.isfinite(a[0]).all() and torch.isfinite(a[1]).all()
+    assert ctx.status() == 0
+
+
+def test_hidden_state_path_end_to_end_with_gradient(ctx):
+    """The whole path without materialised logits: log-probs from hidden states, diagnostics, per-row coefficient,
+    and the gradient w.r.t. hidden states and output embedding, against the oracle's own chain (logits in fp64, its
+    O1-O7 on them, then the read-out's chain rule)."""
+    import oracle.ais_oracle as O
+    from tests import parity as P
+    R, D, V, G, n_resp = 640, 128, 3000, 4, 8
+    hidden, weight, y, _ = make(R, D, V, seed=171)
+    gen = torch.Generator(device="cpu")
+    gen.manual_seed(172)
+    valid = (torch.rand(R, generator=gen) < 0.85).to(torch.uint8)
+    cu = torch.arange(n_resp + 1, dtype=torch.int64) * (R // n_resp)
+    rewards = torch.tensor([1, 0, 0, 1, 0, 1, 1, 0], dtype=torch.float32)
+    inv_t = 1.0 / 0.9
+    p = B.default_params(inv_temperature=inv_t)
+    h64, w64 = f64(hidden), f64(weight)
+    z = L.logits(h64, w64)
+    lp_ref, lse_ref = O.token_logprob(z, y.cpu().numpy(), valid.numpy(), inv_t)
+    rng = np.random.default_rng(173)
+    logp_roll = np.where(valid.numpy() != 0, lp_ref + rng.normal(0, 0.05, size=R), 0.0).astype(np.float32)
+    op = P.oracle_params(p)
+    adv_ref = O.group_advantages(rewards.double().numpy(), G, op.adv_mode, op.eps_std)
+    rd = O.diagnostics(lp_ref, logp_roll, valid.numpy(), cu.numpy(), adv_ref, op)
+    _, _, g_ref = O.loss_and_row_coeff(lp_ref, logp_roll.astype(np.float64), None, None, valid.numpy(), cu.numpy(),
+                                       adv_ref, rd["count"], rd["alpha"], op)
+    dz = O.dlogits_rows(z, lse_ref, y.cpu().numpy(), g_ref, inv_t)             # the logits-based oracle's O7
+    ref_dh, ref_dw = dz @ w64, dz.T @ h64
+    dev = lambda a: torch.from_numpy(a).cuda() if isinstance(a, np.ndarray) else a.cuda()
+    logp, lse = ctx.lm_head_logprob(hidden, weight, y, dev(valid), inv_t)
+    adv, count, diag = ctx.diagnostics(logp, dev(logp_roll), dev(valid), dev(cu), dev(rewards), G, p)
+    loss, wtilde, gcoef = ctx.grpo_row_scale(logp, dev(logp_roll), dev(valid), dev(cu), adv, count, diag, p)
+    dh, dw = ctx.lm_head_grad(hidden, weight, y, lse, logp, gcoef, inv_t, 1024)
+    torch.cuda.synchronize()
+    assert ctx.status() == 0
+    tol_dz = dz_tolerance(dz, None, None, True)
+    # the coefficient itself is held to a relative 1e-3 by its own test; it scales its row of dlogits
+    tol_dz = tol_dz + 1e-3 * np.abs(dz)
+    err_h, err_w = np.abs(f64(dh) - ref_dh), np.abs(f64(dw) - ref_dw)
+    tol_h, tol_w = tol_dz @ np.abs(w64), tol_dz.T @ np.abs(h64)
+    print(f"end to end: worst error / bound dhidden {(err_h / np.maximum(tol_h, 1e-300)).max():.3f} "
+          f"dweight {(err_w / np.maximum(tol_w, 1e-300)).max():.3f}", flush=True)
+    assert np.all(err_h <= tol_h + 1e-30) and np.all(err_w <= tol_w + 1e-30)
+    assert np.abs(ref_dh).max() > 0 and np.all(f64(dh)[valid.numpy() == 0] == 0)
+
+
+def test_full_vocabulary_and_width_every_element(ctx):
+    """The Qwen3-8B read-out shape (d_model 4,096, vocabulary 151,936: 19 chunks of 8,192) on 1,024 rows, a size at
+    which the oracle can still do everything: every element of both gradients is compared."""
+    batch = W.generate_readout(W.config(2), device="cuda", n_rows=1024)
+    R = batch.hidden.shape[0]
+    rng = np.random.default_rng(31)
+    g = (rng.normal(0, 1.0, size=R) * 1e-4).astype(np.float32)
+    g[rng.random(R) < 0.15] = 0.0
+    coeff = torch.from_numpy(g).cuda()
+    logp, lse = ctx.lm_head_logprob(batch.hidden, batch.weight, batch.token_ids, batch.valid)
+    dh, dw = ctx.lm_head_grad(batch.hidden, batch.weight, batch.token_ids, lse, logp, coeff)
+    torch.cuda.synchronize()
+    assert ctx.status() == 0
+    h64, w64 = f64(batch.hidden), f64(batch.weight)
+    dz = L.dlogits(h64, w64, batch.token_ids.cpu().numpy(), g.astype(np.float64), g != 0)
+    tol_dz = dz_tolerance(dz, None, None, True)
+    ref_dh, tol_h = dz @ w64, tol_dz @ np.abs(w64)
+    err_h = np.abs(f64(dh) - ref_dh)
+    worst_h = float((err_h / np.maximum(tol_h, 1e-300)).max())
+    del ref_dh, tol_h
+    ref_dw, tol_w = dz.T @ h64, tol_dz.T @ np.abs(h64)
+    err_w = np.abs(f64(dw) - ref_dw)
+    worst_w = float((err_w / np.maximum(tol_w, 1e-300)).max())
+    print(f"full vocabulary and width, {R} rows: worst error / bound dhidden {worst_h:.3f} dweight {worst_w:.3f}", flush=True)
+    assert worst_h <= 1.0 and worst_w <= 1.0 and np.abs(ref_dw).max() > 0
+    assert np.all(f64(dh)[g == 0] == 0)
+
+
+def test_full_size_properties_and_sampled_rows(ctx):
+    """Workload 2's read-out at full size (41,643 rows), in the configuration the benchmark times.  The oracle
+    evaluates the hidden-state gradient of sampled rows one by one; for the output-embedding gradient, whose every
+    element depends on every row, two properties that hold at any size are checked: sum_v dweight[v, :] = 0 up to
+    the rounding of dlogits (every row of softmax - onehot sums to zero), and <dweight, W> = <dhidden, H> (both
+    equal sum_{n,v} dlogits[n, v] z[n, v]; the two GEMMs consume the same bf16 dlogits, so this holds to the
+    accuracy of their fp32 accumulation)."""
+    batch = W.generate_readout(W.config(2), device="cuda")
+    R, D = batch.hidden.shape
+    V = batch.weight.shape[0]
+    rng = np.random.default_rng(33)
+    g = (rng.normal(0, 1.0, size=R) * 1e-5).astype(np.float32)
+    g[rng.random(R) < 0.1] = 0.0
+    coeff = torch.from_numpy(g).cuda()
+    logp, lse = ctx.lm_head_logprob(batch.hidden, batch.weight, batch.token_ids, batch.valid)
+    dh, dw = ctx.lm_head_grad(batch.hidden, batch.weight, batch.token_ids, lse, logp, coeff)
+    torch.cuda.synchronize()
+    assert ctx.status() == 0 and torch.isfinite(dh).all() and torch.isfinite(dw).all()
+    assert not bool(dh[torch.from_numpy(g == 0).cuda()].any())
+    # sampled rows of dhidden against the oracle
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, R - 257, R - 1], rng.integers(0, R, 10)]))
+    rows = rows[g[rows] != 0]
+    w64 = f64(batch.weight)
+    worst = 0.0
+    for n in rows:
+        h = f64(batch.hidden[n:n + 1])
+        dz = L.dlogits(h, w64, batch.token_ids[n:n + 1].cpu().numpy(), g[n:n + 1].astype(np.float64))
+        ref, tol = dz @ w64, dz_tolerance(dz, None, None, True) @ np.abs(w64)
+        err = np.abs(f64(dh[n:n + 1]) - ref)
+        assert np.all(err <= tol), n
+        worst = max(worst, float((err / tol).max()))
+    # properties of dweight
+    col = dw.double().sum(dim=0)
+    col_abs = dw.double().abs().sum(dim=0)
+    ratio = float((col.abs() / col_abs).max())
+    lhs = float((dw.double() * batch.weight.double()).sum())
+    rhs = float((dh.double() * batch.hidden.double()).sum())
+    scale = float((dh.double() * batch.hidden.double()).abs().sum())
+    print(f"full size: dhidden worst error / bound {worst:.3f} on {len(rows)} rows; |sum_v dweight| / sum_v |dweight| "
+          f"{ratio:.2e}; <dweight, W> {lhs:.6e} <dhidden, H> {rhs:.6e} (sum of |terms| {scale:.3e})", flush=True)
+    assert ratio < 2e-3 and abs(lhs - rhs) <= 1e-4 * scale
