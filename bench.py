@@ -43,17 +43,22 @@ def measured_traffic(kernel: str, workload: int):
 
 
 def cpu_baseline(batch, params, sample_rows: int):
-    """The CPU oracle, as it stands, on the first `sample_rows` rows of the batch (whole responses are
-    not needed: the sample is re-packed as responses of equal length so that every step of the path runs)."""
+    """The CPU oracle, as it stands, on the leading whole prompt groups of the timed batch: their own response
+    boundaries, mask, tokens, rollout log-probs and rewards.  As many groups as fit in `sample_rows` rows, at least
+    one, so every step of the path runs on a part of the very batch the GPU is timed on."""
     import numpy as np
     import oracle.ais_oracle as O
-    from oracle.pool import OraclePool
+    from oracle.pool import OraclePool, widen
 
     shape = batch.shape
     G = shape.group_size
-    n = min(sample_rows, batch.n_rows)
-    n -= n % G
-    per = n // G
+    cu_all = batch.cu_rows.cpu().numpy().astype(np.int64)
+    n_groups_all = (len(cu_all) - 1) // G
+    n_groups = max(1, int(np.searchsorted(cu_all[G::G], sample_rows, side="right")))
+    n_groups = min(n_groups, n_groups_all)
+    n_resp = n_groups * G
+    n = int(cu_all[n_resp])
+    cu = cu_all[:n_resp + 1]
     z = batch.logits[:n]
     dtype = shape.logits_dtype
     bits = (z.view(__import__("torch").int16).cpu().numpy().view(np.uint16) if dtype == "bf16"
@@ -61,8 +66,7 @@ def cpu_baseline(batch, params, sample_rows: int):
     y = batch.token_ids[:n].cpu().numpy()
     valid = batch.valid[:n].cpu().numpy()
     lp_roll = batch.logp_roll[:n].double().cpu().numpy()
-    cu = np.arange(G + 1, dtype=np.int64) * per
-    rewards = np.array([1.0, 0.0] * (G // 2) + [1.0] * (G % 2))
+    rewards = batch.rewards[:n_resp].double().cpu().numpy()
     workers = min(16, len(os.sched_getaffinity(0)))
     pool = OraclePool(workers)
     try:
@@ -73,19 +77,22 @@ def cpu_baseline(batch, params, sample_rows: int):
     finally:
         pool.close()
     n_valid = int(valid.astype(bool).sum())
-    # the same oracle in this process alone, on a sixteenth of the sample, for a per-core figure
-    m = max(G, (n // 16) - (n // 16) % G)
-    from oracle.pool import widen
-    zs = widen(bits[:m], dtype)
+    # the same oracle in this process alone, on the leading rows of each response of the first group (a sixteenth of
+    # the sample at most), for a per-core figure
+    m_per = max(1, min(int(np.diff(cu[:G + 1]).min()), max(1, n // (16 * G))))
+    rows = np.concatenate([np.arange(cu[i], cu[i] + m_per) for i in range(G)])
+    zs = widen(bits[rows], dtype)
     t0 = time.perf_counter()
-    O.ais_grpo(zs, y[:m], valid[:m], np.arange(G + 1, dtype=np.int64) * (m // G), lp_roll[:m], rewards, G,
+    O.ais_grpo(zs, y[rows], valid[rows], np.arange(G + 1, dtype=np.int64) * m_per, lp_roll[rows], rewards[:G], G,
                O.Params(**params))
     dt1 = time.perf_counter() - t0
     return {"value": n_valid / dt, "unit": "tokens/s", "cores": workers, "kind": "oracle",
-            "sample": f"first {n} rows ({n_valid} valid) of the same batch as {G} equal-length responses, "
-                      f"numpy fp64 oracle over {workers} worker processes, {dt:.2f} s wall",
-            "single_core": {"value": int(valid[:m].astype(bool).sum()) / dt1, "unit": "tokens/s",
-                            "sample": f"first {m} rows in one process, {dt1:.2f} s wall"}}
+            "sample": f"the first {n_groups} of {n_groups_all} prompt groups of the timed batch ({n_resp} responses, {n} rows, "
+                      f"{n_valid} valid, their own boundaries and rewards), numpy fp64 oracle over {workers} worker "
+                      f"processes, {dt:.2f} s wall",
+            "single_core": {"value": int(valid[rows].astype(bool).sum()) / dt1, "unit": "tokens/s",
+                            "sample": f"the leading {m_per} rows of each response of the first group in one process, "
+                                      f"{dt1:.2f} s wall"}}
 
 
 def burst_class(vocab: int, esize: int) -> str:
@@ -195,7 +202,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="headline workload 1..5 (2 = Qwen3-8B-shaped, V = 151,936)")
     ap.add_argument("--others", type=str, default="1,3,4,5",
                     help="workloads also timed and listed under `workloads` (comma-separated, empty = none)")
-    ap.add_argument("--cpu-rows", type=int, default=8192, help="rows of the batch the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=24000,
+                    help="the CPU oracle is timed on the leading whole prompt groups within this many rows, at least one (0 = skip)")
     ap.add_argument("--in-place", action="store_true", help="write the gradient over the logits")
     ap.add_argument("--extras", action="store_true",
                     help="also time the FP8 rollout-perturbation kernels on the same batch (reported under next_rows)")
