@@ -67,6 +67,11 @@ ScopedTimer::~ScopedTimer() {
 
 namespace {
 
+// Clears an output with a kernel: a caller may be recording the stream into a graph, where memset nodes are avoided.
+__global__ __launch_bounds__(256) void zero_fill_kernel(float* __restrict__ out, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) out[i] = 0.f;
+}
+
 struct DeviceGuard {
   int prev = -1;
   bool ok = true;
@@ -518,8 +523,12 @@ int ais_lm_head_grad(ais_ctx* ctx, const void* hidden, long long hidden_stride, 
   if (!std::isfinite(inv_temperature) || inv_temperature <= 0.f) return AIS_ERR_PARAM;
   if (ctx == nullptr) return AIS_ERR_NULL;
   DeviceGuard guard(ctx->device);
-  const size_t dw_bytes = sizeof(float) * (size_t)vocab * (size_t)d_model;
-  if (n_rows == 0) return hip_fail(ctx, hipMemsetAsync(dweight_out, 0, dw_bytes, ctx->stream));
+  if (n_rows == 0) {                   // no rows: the embedding gradient is zero, there is no hidden-state gradient
+    const size_t n = (size_t)vocab * (size_t)d_model;
+    const unsigned blocks = (unsigned)std::min<size_t>((n + 255) / 256, (size_t)ctx->n_cus * 8);
+    zero_fill_kernel<<<blocks, 256, 0, ctx->stream>>>(dweight_out, n);
+    return hip_fail(ctx, hipGetLastError());
+  }
   if (chunk_vocab > ((vocab + 255) / 256) * 256) chunk_vocab = ((vocab + 255) / 256) * 256;
   // workspace: the chunk's dlogits, then the device-side decomposition of the recompute kernel
   const size_t ds_bytes = ((size_t)n_rows * (size_t)chunk_vocab * 2 + 255) & ~size_t(255);

@@ -212,3 +212,17 @@ def test_full_size_properties_and_sampled_rows(ctx):
     print(f"full size: dhidden worst error / bound {worst:.3f} on {len(rows)} rows; |sum_v dweight| / sum_v |dweight| "
           f"{ratio:.2e}; <dweight, W> {lhs:.6e} <dhidden, H> {rhs:.6e} (sum of |terms| {scale:.3e})", flush=True)
     assert ratio < 2e-3 and abs(lhs - rhs) <= 1e-4 * scale
+
+
+def test_empty_batch(ctx):
+    """No rows: the embedding gradient is all zeros (written by a kernel, the output starts as garbage), the
+    hidden-state gradient is empty, and nothing faults."""
+    D, V = 64, 700
+    weight = torch.randn(V, D, device="cuda").to(torch.bfloat16)
+    hidden = torch.empty((0, D), device="cuda", dtype=torch.bfloat16)
+    i32 = torch.empty(0, device="cuda", dtype=torch.int32)
+    f32 = torch.empty(0, device="cuda", dtype=torch.float32)
+    dh, dw = ctx.lm_head_grad(hidden, weight, i32, f32, f32, f32)
+    torch.cuda.synchronize()
+    assert dh.shape == (0, D) and dw.shape == (V, D) and not bool(dw.any())
+    assert ctx.status() == 0
