@@ -174,6 +174,22 @@ def time_workload(torch, binding, workloads, ctx, k, steps, warmup, mode="ais", 
     d = ctx.read_diag(diag)
     assert ctx.status() == 0
     ms_step = t_total / steps * 1e3
+    # The same step recorded once into a HIP graph and replayed: what a caller whose batches are small enough to be
+    # bound by launches gains (reported beside the eager figure, which stays the headline).
+    ms_graph = None
+    if not in_place:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms_graph = (time.perf_counter() - t0) / steps * 1e3
+        del graph
+        assert ctx.status() == 0
     fwd_bytes = e * V * N                                   # one read of every valid row
     bwd_bytes = 2 * e * V * N + e * V * (R - N)             # read + write of valid rows, zero-fill of the others
     fwd_gbps = fwd_bytes / (ms_fwd / n_fwd * 1e-3) / 1e9
@@ -182,7 +198,7 @@ def time_workload(torch, binding, workloads, ctx, k, steps, warmup, mode="ais", 
     summary = {
         "k": k, "workload": f"config {k}: {shape.name}", "vocab": V, "rows": R, "valid_rows": N, "responses": shape.n_resp,
         "group_size": shape.group_size, "logits": shape.logits_dtype, "layout": shape.layout,
-        "ms_per_step": ms_step, "tokens_per_s": N / (ms_step * 1e-3),
+        "ms_per_step": ms_step, "tokens_per_s": N / (ms_step * 1e-3), "ms_per_step_hip_graph": ms_graph,
         "path_hbm": {"GB/s": path_gbps, "frac": path_gbps / HBM_PEAK_GBPS, "bytes_per_step": fwd_bytes + bwd_bytes},
         "dominant_kernel": {"name": burst_class(V, e), "avg_ms": ms_bwd / n_bwd, "bytes_per_launch": bwd_bytes,
                             "GB/s": bwd_gbps, "frac": bwd_gbps / HBM_PEAK_GBPS,
@@ -269,7 +285,7 @@ def main():
         "kernels": {"token_logprob": head["token_logprob"],
                     "dlogits": {q: dom[q] for q in ("avg_ms", "GB/s", "frac")},
                     "copy_yardstick": {"avg_ms": ms_copy / n_copy, "GB/s": copy_gbps}},
-        "path_hbm": head["path_hbm"],
+        "path_hbm": head["path_hbm"], "ms_per_step_hip_graph": head["ms_per_step_hip_graph"],
         "diag": head["diag"], "loss": head["loss"], "gen_s": head["gen_s"],
         "workloads": [dict(w, dominant_kernel=dict(w["dominant_kernel"],
                                                     traffic=measured_traffic("dlogits_burst_kernel", w["k"])))
