@@ -74,13 +74,15 @@ def test_random_rows(ctx, dtype, vocab):
     assert np.abs(lp.double().cpu().numpy() - ref).max() <= LOGP_ATOL
 
 
-# every instantiation of the table kernels for bf16 rows (4 / 8 / 12 / 16 / 18 / 19 / 20 / 24 vectors per lane), of the
-# register-resident quantise kernel that fp32 rows and wider bf16 rows take: 4 / 8 / 12 / 16 / 20 / 24 vectors per lane, 18 + 9,
-# 22 + 9 and 24 + 9 with the last nine in LDS, and the streaming route beyond; and of the burst dequantise kernel:
-# 4 / 8 / 12 / 16 / 19 / 20 vectors per lane in one burst, two and three bursts of 16, and the streaming route beyond
-# 48 (a vector holds 8 bf16 or 4 fp32 elements)
-ROW_VOCABS = {"bf16": [40_001, 90_007, 120_011, 140_001, 151_936, 160_003, 190_003, 210_007, 248_320, 260_011, 270_336, 275_003,
-                       400_003],
+# every instantiation of the table kernels for bf16 rows (quantise: 4 / 8 / 12 / 16 / 18 / 19 / 20 / 24 vectors per lane;
+# rollout log-prob: the same up to 20, then 21 / 22 / 23 in registers, 23 + 4 and 23 + 8 with the last ones in LDS
+# slots: 190,003 ... 253,952 logits, and the two-read streaming route beyond), of the register-resident quantise kernel
+# that fp32 rows and wider bf16 rows take: 4 / 8 / 12 / 16 / 20 / 24 vectors per lane, 18 + 9, 22 + 9 and 24 + 9 with
+# the last nine in LDS, and the streaming route beyond; and of the burst dequantise kernel: 4 / 8 / 12 / 16 / 19 / 20
+# vectors per lane in one burst, two and three bursts of 16, and the streaming route beyond 48 (a vector holds 8 bf16
+# or 4 fp32 elements)
+ROW_VOCABS = {"bf16": [40_001, 90_007, 120_011, 140_001, 151_936, 160_003, 170_003, 178_003, 186_011, 188_416, 190_003,
+                       210_007, 221_184, 221_192, 248_320, 253_951, 253_952, 253_960, 260_011, 270_336, 275_003, 400_003],
               "f32": [20_011, 45_007, 60_013, 75_011, 80_021, 95_003, 105_001, 124_003, 130_007, 135_168, 137_501,
                       200_003]}
 
@@ -228,9 +230,40 @@ def test_rollout_logprob_equals_generator_and_masks(ctx):
         assert ctx.status() == 0
 
 
-def test_full_size_rows_sampled(ctx):
-    """Workload 2 at full size: codes of sampled rows are bit-exact, scales of all rows are bit-exact."""
-    b = W.generate(W.config(2), "cuda", row_chunk=512)
+def test_wide_rows_many_per_workgroup(ctx):
+    """V = 248,320 (23 vectors per lane in registers + 8 in LDS slots) on more rows than there are compute units, a
+    fifth of them masked: every workgroup of the persistent grid walks several rows, refilling registers and slots
+    with the next row while it sums the current one.  Every evaluated row against the oracle."""
+    R, V = 700, 248_320
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4)
+    z = torch.empty(R, V, device="cuda", dtype=torch.bfloat16)
+    for r0 in range(0, R, 100):
+        z[r0:r0 + 100] = (torch.randn(100, V, generator=g, device="cuda") * 2.5).to(torch.bfloat16)
+    y = torch.randint(0, V, (R,), generator=g, device="cuda", dtype=torch.int32)
+    z[torch.arange(R, device="cuda"), y.long()] += 6.0
+    z[::7, V - 1] = 30.0                                  # abs-max in the last vector, held in the last slot
+    valid = (torch.rand(R, generator=g, device="cuda") < 0.8).to(torch.uint8)
+    lp = ctx.fp8_rollout_logprob(z, y, valid)
+    torch.cuda.synchronize()
+    assert ctx.status() == 0
+    lp = lp.double().cpu().numpy()
+    v = valid.cpu().numpy().astype(bool)
+    assert np.all(lp[~v] == 0)
+    worst = 0.0
+    for r0 in range(0, R, 50):
+        ref = F.rollout_logprob(z[r0:r0 + 50].float().cpu().numpy(), y[r0:r0 + 50].cpu().numpy(),
+                                valid[r0:r0 + 50].cpu().numpy())
+        worst = max(worst, float(np.abs(lp[r0:r0 + 50] - ref).max()))
+    print(f"worst |logp - oracle| over {int(v.sum())} rows: {worst:.2e}", flush=True)
+    assert worst <= LOGP_ATOL
+
+
+@pytest.mark.parametrize("k", [2, 4])
+def test_full_size_rows_sampled(ctx, k):
+    """Workloads 2 and 4 at full size: codes of sampled rows are bit-exact, scales of all rows are bit-exact, the
+    rollout log-prob of sampled rows equals the oracle's and that of every row the generator's."""
+    b = W.generate(W.config(k), "cuda", row_chunk=512)
     codes, scale = ctx.fp8_quantize_rows(b.logits)
     lp = ctx.fp8_rollout_logprob(b.logits, b.token_ids, b.valid)
     torch.cuda.synchronize()
