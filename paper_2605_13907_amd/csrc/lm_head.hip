@@ -17,17 +17,19 @@
 // subtracts.  Workgroups are numbered so that those resident on one XCD (which share an L2) work on a few
 // token blocks x all vocabulary chunks at the same time, and therefore share both operands.
 //
-// Two kernels do the tile arithmetic.  The streaming kernel (d_model a multiple of 32) copies operand slices
-// from global memory straight into a ring of LDS stages and interleaves copies, LDS reads and MFMAs one by
-// one; the register-staged kernel accepts any d_model that is a multiple of 8.  Both keep the operand slices
-// in LDS with an XOR swizzle of their 16-byte chunks, which makes the fragment reads free of bank conflicts
-// (measured: none).
+// Three kernels do the tile arithmetic.  The streaming kernels copy operand slices from global memory straight into
+// LDS and interleave copies, LDS reads and MFMAs one by one: slices of 64 elements of d_model in two buffers when
+// d_model is a multiple of 64 (a row of a slice is then a whole 128-byte line: half the L2 requests of 64-byte
+// rows for the same bytes), slices of 32 elements in a ring of four stages when it is a multiple of 32; the
+// register-staged kernel accepts any d_model that is a multiple of 8.  All keep the operand slices in LDS with an
+// XOR swizzle of their 16-byte chunks, which makes the fragment reads free of bank conflicts (measured: none).
 //
-// What bounds it.  With 256 x 256 tiles every MFMA needs 256 bytes from L2, and under a sustained run with
-// real (toggling) data the part is power-limited: the shader clock settles near 1.6-1.8 GHz instead of 2.4,
-// and time follows energy rather than cycle counts (shaving cycles per step lowered the clock by the same
-// factor).  Measured at the Qwen3-8B shape: about 1.17 PFLOP/s, against 1.43 PFLOP/s for the library GEMM
-// that materialises the logits.
+// What bounds it.  With 256 x 256 tiles every MFMA needs 256 bytes from L2 and, with 128 x 64 outputs per wavefront,
+// 768 bytes of fragments from LDS; under a sustained run with real (toggling) data the part is also power-limited
+// (the shader clock settles near 1.7 GHz instead of 2.4).  Measured at the Qwen3-8B shape on one device: 41.0-41.5 ms
+// with 64-element slices (1.25-1.26 PFLOP/s), 43.4 ms with 32-element slices; the same kernel with the copies left
+// out (wrong results, timing only) 34.3 ms, with every copy fetching a slice that is already in L2 39.1 ms; the
+// library GEMM that materialises the logits 34.5 ms (1.50 PFLOP/s).
 #include "ais_internal.h"
 #include "device_utils.h"
 
@@ -535,6 +537,199 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_stream_kernel(
   if (!GRAD) sm.finish(it, reinterpret_cast<float*>(lds), n_rows, part_m, part_s);
 }
 
+// ---- streaming kernel with 64-element steps: d_model a multiple of 64 -------------------------------------------
+// The same arithmetic on slices of 64 elements of d_model: a row of a slice is then a whole 128-byte line, so a copy
+// instruction of a wavefront asks L2 for 8 full lines instead of 16 half lines (half the requests for the same
+// bytes).  Two buffers of 64 KiB (W slice, H slice, 128-byte rows, chunks swizzled as in lds_chunk_offset below).  A
+// step has four sub-steps of 16 elements; the fragments of a sub-step are read during the one before it.  One
+// barrier per step, after the second MFMA of its last sub-step: every wavefront has then issued all its reads of
+// the step's buffer and has waited for its own copies of the next step, so the barrier publishes the next step and
+// frees the buffer; the copies of the step after next go into it at once (four in the rest of this step, four in the
+// first sub-step of the next), a whole step before they are awaited.
+constexpr int kS64K = 64;
+constexpr int kS64OperandBytes = kLmTileV * kS64K * 2;           // 32 KiB
+constexpr int kS64BufferBytes = 2 * kS64OperandBytes;            // 64 KiB
+constexpr int kS64LdsBytes = 2 * kS64BufferBytes;                // 128 KiB
+
+__device__ __forceinline__ int s64_chunk_offset(int row, int c) { return row * 128 + ((c ^ ((row >> 1) & 7)) << 4); }
+
+template <bool GRAD>
+__global__ __launch_bounds__(kLmThreads) void lm_head_stream64_kernel(
+    const bf16_t* __restrict__ hidden, long long ld_h, const bf16_t* __restrict__ weight, long long ld_w,
+    LmRows rows, const LmDevPlan* __restrict__ plan, int d_model, int vocab, const int* __restrict__ token_ids,
+    float scale, int n_vtiles, float* __restrict__ part_m, float* __restrict__ part_s,
+    float* __restrict__ zy_out, LmGradArgs ga) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  LmItem it;
+  if (!it.init(plan, n_vtiles)) return;
+  const int n_rows = rows.n_rows;
+  const int lane = it.lane, wave = it.wave;
+
+  // ---- copies: wavefront w moves rows 8 w .. 8 w + 7 (+ 64 j, j = 0..3) of each slice; a lane sits at chunk
+  // position lane & 7 of row lane >> 3 and therefore fetches logical chunk (lane & 7) ^ ((row >> 1) & 7), which is
+  // the same for the four rows 64 apart
+  const int crow = 8 * wave + (lane >> 3);
+  const int cchunk = (lane & 7) ^ ((crow >> 1) & 7);
+  const bf16_t* hp[4];
+  const bf16_t* wp[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int trow = rows.row(it.t0 + crow + 64 * j, it.n_eval);
+    hp[j] = hidden + (long long)trow * ld_h + cchunk * 8;
+  }
+  auto point_w = [&](int vt) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int vrow = min(vt * kLmTileV + crow + 64 * j, vocab - 1);
+      wp[j] = weight + (long long)vrow * ld_w + cchunk * 8;
+    }
+  };
+  const int n_ksteps = d_model / kS64K;
+  const int n_steps = (it.vt1 - it.vt0) * n_ksteps;
+  // cursor of the step being copied
+  int c_step = 0, c_kt = 0, c_vt = it.vt0;
+  point_w(c_vt);
+  // One of the eight copy instructions (W rows, H rows, then the same 64, 128 and 192 rows further) that bring the
+  // cursor's step into buffer `buf`; the eighth advances the cursor.  Once the cursor has reached the last step it
+  // stays there: the copies issued after that re-fetch the last step into a buffer nobody reads any more, which
+  // keeps the loop free of branches.
+  auto copy_part = [&](int buf, int q) {
+    unsigned char* base = lds + buf * kS64BufferBytes + (8 * wave + 64 * (q >> 1)) * 128;
+    const int k0 = c_kt * kS64K;
+    if ((q & 1) == 0)
+      __builtin_amdgcn_global_load_lds((glb_ptr)(wp[q >> 1] + k0), (lds_ptr)base, 16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds((glb_ptr)(hp[q >> 1] + k0), (lds_ptr)(base + kS64OperandBytes), 16, 0, 0);
+    if (q == 7 && c_step + 1 < n_steps) {
+      ++c_step;
+      if (++c_kt == n_ksteps) {
+        c_kt = 0;
+        ++c_vt;
+        point_w(c_vt);
+      }
+    }
+  };
+
+  // ---- fragments: lane reads row (32-row tile base + col), chunk 2 kk + half of a 128-byte row
+  int frag_off[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) frag_off[kk] = s64_chunk_offset(it.col, 2 * kk + it.half);
+  const int a_base = it.wv * kLmWaveV * 128;
+  const int b_base = kS64OperandBytes + it.wt * kLmWaveT * 128;
+  // One fragment read, in the order the MFMAs need them: a0 b0 b1 a1 a2 a3 (r = 0..5).
+  auto read_frag = [&](int step, int kk, int r, bf16x8 (&a)[4], bf16x8 (&b)[2]) {
+    const unsigned char* base = lds + (step & 1) * kS64BufferBytes + frag_off[kk];
+    if (r == 1 || r == 2)
+      b[r - 1] = as_bf16x8(*reinterpret_cast<const u32x4*>(base + b_base + (r - 1) * 4096));
+    else {
+      const int i = r == 0 ? 0 : r - 2;
+      a[i] = as_bf16x8(*reinterpret_cast<const u32x4*>(base + a_base + i * 4096));
+    }
+  };
+  // Which fragment reads follow MFMA q of a sub-step: two after each of the first two, one after the next two.
+  auto reads_after = [&](int q, int step, int kk, bf16x8 (&a)[4], bf16x8 (&b)[2]) {
+    if (q == 0) { read_frag(step, kk, 0, a, b); read_frag(step, kk, 1, a, b); }
+    if (q == 1) { read_frag(step, kk, 2, a, b); read_frag(step, kk, 3, a, b); }
+    if (q == 2) read_frag(step, kk, 4, a, b);
+    if (q == 3) read_frag(step, kk, 5, a, b);
+  };
+
+  LmAcc acc;
+  lm_clear(acc);
+  auto mfma_one = [&](const bf16x8 (&a)[4], const bf16x8 (&b)[2], int q) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        if (2 * i + j == q) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+  };
+  LmSoftmax sm;
+  LmGrad gr;
+  if (GRAD) gr.init(it, rows, vocab, token_ids, ga);
+  else sm.init(it, rows, vocab, token_ids);
+  auto tile_done = [&](int tile) {
+    if (GRAD) gr.emit(acc, it, tile, vocab, scale, ga);
+    else sm.fold(acc, it, tile, vocab, scale, zy_out);
+  };
+
+#define AIS_PIN __builtin_amdgcn_sched_barrier(0)
+  // Copies of the step after next issued in the rest of a step, right after its barrier (the others follow in the
+  // first sub-step of the next step), and MFMAs of the last sub-step issued before the barrier.  Measured at 41,643
+  // rows x 151,936 x 4,096 on one device: (4, 2) 41.0 ms; (6, 2) 41.1; (0, 2) 42.0; (4, 4) 40.7; (6, 1) 40.7.
+  constexpr int kTailCopies = 4;
+  constexpr int kPB = 2;
+  static_assert(kPB >= 1 && kPB <= 4, "four MFMAs after the barrier carry the reads of the next sub-step");
+  static_assert(kTailCopies >= 0 && kTailCopies <= 8 - kPB && (kTailCopies % 2) == 0, "one copy per MFMA of the tail");
+  bf16x8 a0[4], b0[2], a1[4], b1[2];
+  int vt = it.vt0, kt = 0;
+  // ---- prologue: step 0 and the first half of step 1's copies in flight, step 0 published
+#pragma unroll
+  for (int q = 0; q < 8; ++q) copy_part(0, q);
+#pragma unroll
+  for (int q = 0; q < kTailCopies; ++q) copy_part(1, q);
+  // copies complete in order: step 0 has landed
+  if (kTailCopies == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+  else if (kTailCopies == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  else if (kTailCopies == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 6; ++r) read_frag(0, 0, r, a0, b0);
+  for (int s = 0; s < n_steps; ++s) {
+    // sub-step 0, with the second half of the next step's copies
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      mfma_one(a0, b0, q);
+      AIS_PIN;
+      reads_after(q, s, 1, a1, b1);
+      AIS_PIN;
+      if (q < 8 - kTailCopies) copy_part((s + 1) & 1, kTailCopies + q);
+      AIS_PIN;
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      mfma_one(a1, b1, q);
+      AIS_PIN;
+      reads_after(q, s, 2, a0, b0);
+      AIS_PIN;
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      mfma_one(a0, b0, q);
+      AIS_PIN;
+      reads_after(q, s, 3, a1, b1);
+      AIS_PIN;
+    }
+    // last sub-step: two MFMAs give the matrix cores work while the wavefronts gather; then this wavefront's copies
+    // of step s + 1 must have landed (all of them: nothing younger is in flight) and everyone meets.  Written as one
+    // opaque instruction pair, like the barrier of the 32-element kernel.
+#pragma unroll
+    for (int q = 0; q < kPB; ++q) mfma_one(a1, b1, q);
+    AIS_PIN;
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    AIS_PIN;
+#pragma unroll
+    for (int q = kPB; q < 8; ++q) {
+      mfma_one(a1, b1, q);
+      AIS_PIN;
+      reads_after(q - kPB, s + 1, 0, a0, b0);
+      AIS_PIN;
+      if (q >= 8 - kTailCopies) copy_part(s & 1, q - (8 - kTailCopies));
+      AIS_PIN;
+    }
+    if (++kt == n_ksteps) {
+      tile_done(vt);
+      lm_clear(acc);
+      kt = 0;
+      ++vt;
+    }
+  }
+#undef AIS_PIN
+  // copies of the last steps may still be in flight, and they land in LDS that finish() is about to reuse
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if (!GRAD) sm.finish(it, reinterpret_cast<float*>(lds), n_rows, part_m, part_s);
+}
+
 // ---- register-staged kernel: any d_model that is a multiple of 8 ---------------------------------------------
 // Steps of 64 elements; the last step's chunks past the end of d_model must become zeros, so the slices are
 // loaded into registers before the arithmetic of a step and written to the other of two LDS buffers in the
@@ -784,10 +979,12 @@ int launch_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long ld_h, con
                            float* part_m, float* part_s, float* zy, int* row_index, int* row_pos, void* dev_plan,
                            float* logp_out, float* lse_out) {
   constexpr int kStreamLds = AIS_LM_STAGES * kStStageBytes;
-  static std::once_flag once_stream[kMaxDevices], once_staged[kMaxDevices];   // per function and device
-  static bool ok_stream[kMaxDevices], ok_staged[kMaxDevices];
+  static std::once_flag once_stream[kMaxDevices], once_s64[kMaxDevices], once_staged[kMaxDevices];   // per function and device
+  static bool ok_stream[kMaxDevices], ok_s64[kMaxDevices], ok_staged[kMaxDevices];
   if (!allow_dynamic_lds(ctx, reinterpret_cast<const void*>(lm_head_stream_kernel<AIS_LM_STAGES, false>), kStreamLds,
                          once_stream, ok_stream) ||
+      !allow_dynamic_lds(ctx, reinterpret_cast<const void*>(lm_head_stream64_kernel<false>), kS64LdsBytes, once_s64,
+                         ok_s64) ||
       !allow_dynamic_lds(ctx, reinterpret_cast<const void*>(lm_head_staged_kernel), kLmLdsBytes, once_staged,
                          ok_staged))
     return hip_fail(ctx, hipErrorInvalidValue);
@@ -802,7 +999,11 @@ int launch_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long ld_h, con
   LmRows rows{valid != nullptr ? row_index : nullptr, (int)n_rows};
   {
     ScopedTimer timer(ctx, AIS_K_LM_HEAD);
-    if (d_model % kStK == 0)
+    if (d_model % kS64K == 0)
+      lm_head_stream64_kernel<false><<<max_items, kLmThreads, kS64LdsBytes, ctx->stream>>>(
+          static_cast<const bf16_t*>(hidden), ld_h, static_cast<const bf16_t*>(weight), ld_w, rows, dplan, d_model,
+          vocab, token_ids, inv_temperature * kLog2e, plan.n_vtiles, part_m, part_s, zy, LmGradArgs{});
+    else if (d_model % kStK == 0)
       lm_head_stream_kernel<AIS_LM_STAGES, false><<<max_items, kLmThreads, kStreamLds, ctx->stream>>>(
           static_cast<const bf16_t*>(hidden), ld_h, static_cast<const bf16_t*>(weight), ld_w, rows, dplan, d_model,
           vocab, token_ids, inv_temperature * kLog2e, plan.n_vtiles, part_m, part_s, zy, LmGradArgs{});
@@ -827,10 +1028,11 @@ int launch_lm_head_dlogits_chunk(ais_ctx* ctx, const void* hidden, long long ld_
                                  const int* token_ids, const float* lse, const float* logp, const float* coeff,
                                  float inv_temperature, void* dev_plan, void* ds, long long ds_stride) {
   constexpr int kStreamLds = AIS_LM_STAGES * kStStageBytes;
-  static std::once_flag once[kMaxDevices];
-  static bool ok[kMaxDevices];
+  static std::once_flag once[kMaxDevices], once64[kMaxDevices];
+  static bool ok[kMaxDevices], ok64[kMaxDevices];
   if (!allow_dynamic_lds(ctx, reinterpret_cast<const void*>(lm_head_stream_kernel<AIS_LM_STAGES, true>), kStreamLds,
-                         once, ok))
+                         once, ok) ||
+      !allow_dynamic_lds(ctx, reinterpret_cast<const void*>(lm_head_stream64_kernel<true>), kS64LdsBytes, once64, ok64))
     return hip_fail(ctx, hipErrorInvalidValue);
   const LmHeadPlan plan = lm_head_plan(n_rows, vocab, ctx->n_cus);
   const int max_items = ((plan.n_tblocks * plan.n_chunks + 7) / 8) * 8;
@@ -843,9 +1045,14 @@ int launch_lm_head_dlogits_chunk(ais_ctx* ctx, const void* hidden, long long ld_
   LmGradArgs ga{lse, logp, coeff, static_cast<bf16_t*>(ds), ds_stride, y_off};
   {
     ScopedTimer timer(ctx, AIS_K_LM_HEAD_GRAD);
-    lm_head_stream_kernel<AIS_LM_STAGES, true><<<max_items, kLmThreads, kStreamLds, ctx->stream>>>(
-        static_cast<const bf16_t*>(hidden), ld_h, static_cast<const bf16_t*>(weight), ld_w, rows, dplan, d_model,
-        vocab, token_ids, inv_temperature * kLog2e, plan.n_vtiles, nullptr, nullptr, nullptr, ga);
+    if (d_model % kS64K == 0)
+      lm_head_stream64_kernel<true><<<max_items, kLmThreads, kS64LdsBytes, ctx->stream>>>(
+          static_cast<const bf16_t*>(hidden), ld_h, static_cast<const bf16_t*>(weight), ld_w, rows, dplan, d_model,
+          vocab, token_ids, inv_temperature * kLog2e, plan.n_vtiles, nullptr, nullptr, nullptr, ga);
+    else
+      lm_head_stream_kernel<AIS_LM_STAGES, true><<<max_items, kLmThreads, kStreamLds, ctx->stream>>>(
+          static_cast<const bf16_t*>(hidden), ld_h, static_cast<const bf16_t*>(weight), ld_w, rows, dplan, d_model,
+          vocab, token_ids, inv_temperature * kLog2e, plan.n_vtiles, nullptr, nullptr, nullptr, ga);
   }
   return hip_fail(ctx, hipGetLastError());
 }
