@@ -264,7 +264,8 @@ int ais_fp8_quantize_rows(ais_ctx* ctx, const void* logits, ais_dtype dtype, lon
                           long long vocab, long long row_stride, unsigned char* codes_out,
                           long long codes_stride, float* scale_out);
 
-/* out[n, v] = s_n * value(code[n, v]) in fp32, stored as `out_dtype` (bf16: rounded to nearest even).
+/* The other half of Eq. 1's round trip (Sec. 2.1): the rollout engine's view of the logits,
+ *   out[n, v] = s_n * value(code[n, v])  in fp32, stored as `out_dtype` (bf16: rounded to nearest even).
  * Errors: NULL pointers, sizes, strides < vocab, unknown dtype, misaligned out. */
 int ais_fp8_dequantize_rows(ais_ctx* ctx, const unsigned char* codes, long long codes_stride,
                             const float* scale, long long n_rows, long long vocab, void* out,

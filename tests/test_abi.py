@@ -30,6 +30,25 @@ def test_every_declared_symbol_is_exported():
     assert set(names) == set(B.SYMBOLS), "binding and header disagree on the set of functions"
 
 
+def test_every_compute_entry_point_cites_the_passage_it_implements():
+    """The comment in front of each declaration that computes something names the section, equation or algorithm of
+    the paper that defines the operation; the entry point that allocates nothing names the callers it is for."""
+    import re
+    text = HEADER
+    helpers = {"ais_create", "ais_destroy", "ais_set_stream", "ais_params_default", "ais_strerror",
+               "ais_last_hip_error", "ais_status", "ais_version", "ais_profile", "ais_profile_read", "ais_copy"}
+    for name in declared_functions():
+        if name in helpers:
+            continue
+        at = re.search(r"^[a-z].*\b%s\(" % name, text, re.M).start()
+        comment = text[text.rfind("/*", 0, at):at]
+        assert text.rfind("*/", 0, at) > text.rfind("/*", 0, at), name
+        if name == "ais_diagnostics_static":
+            assert "cannot" in comment and "allocate" in comment, name
+        else:
+            assert re.search(r"\b(Alg\.|Eq\.|Sec\.)", comment), f"{name}: no citation in its comment"
+
+
 def test_struct_sizes_match_header_layout():
     assert C.sizeof(B.AisParams) == 40          # 9 floats + 1 int
     assert C.sizeof(B.AisDiag) == 8 + 15 * 8 + 8
