@@ -123,7 +123,7 @@ def group_advantages(rewards, group_size: int, adv_mode: int = 0, eps_std: float
 
 
 def rows_to_responses(cu_rows, n_rows: int):
-    """seq[n] = index of the response that owns row n."""
+    """seq[n] = index of the response that owns row n (the o_i of Eq. 19 that token position n belongs to)."""
     cu = np.asarray(cu_rows).astype(np.int64)
     seq = np.zeros(n_rows, dtype=np.int64)
     for i in range(cu.size - 1):
@@ -249,7 +249,8 @@ def loss_and_row_coeff(logp, logp_roll, logp_old, logp_ref, valid, cu_rows, adv,
 
 # --------------------------------------------------------------------------- O7
 def dlogits_rows(z, lse, y, g, inv_temperature: float = 1.0):
-    """d loss / d z for a block of rows: g_n inv_T (exp(inv_T z - lse) - onehot(y_n)); rows with g_n = 0 are 0."""
+    """d loss / d z for a block of rows, the chain rule on Eq. 19 through log pi = z_y / T - lse (Alg. 1, "Policy
+    Update"): g_n inv_T (exp(inv_T z - lse) - onehot(y_n)); rows with g_n = 0 are 0."""
     z = _f64(z)
     R, V = z.shape
     g = _f64(g)
@@ -266,7 +267,8 @@ def dlogits_rows(z, lse, y, g, inv_temperature: float = 1.0):
 # ----------------------------------------------------------------- whole path
 def ais_grpo(z, y, valid, cu_rows, logp_roll, rewards, group_size: int, p: Optional[Params] = None,
              logp_old=None, logp_ref=None, want_dz: bool = True):
-    """O1 ... O7 on one batch.  Returns a dict with every intermediate."""
+    """O1 ... O7 on one batch: Alg. 1 from "Compute full-precision log-probs" through "Policy Update" (Eq. 3, 7, 10,
+    12-19) in the paper's order.  Returns a dict with every intermediate."""
     p = p or Params()
     logp, lse = token_logprob(z, y, valid, p.inv_temperature)
     adv = group_advantages(rewards, group_size, p.adv_mode, p.eps_std)

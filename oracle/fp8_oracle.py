@@ -22,7 +22,8 @@ E4M3_MAX = 448.0
 
 
 def e4m3_decode_table() -> np.ndarray:
-    """The value of each of the 256 codes (NaN for the two NaN codes), as float64."""
+    """The value of each of the 256 codes (NaN for the two NaN codes), as float64: the grid that stands in for the
+    integer grid of Eq. 1 when the rollout engine runs in FP8 (Sec. 2.1), from the published E4M3 "fn" format."""
     out = np.empty(256)
     for code in range(256):
         s, e, m = code >> 7, (code >> 3) & 0xF, code & 7
@@ -37,7 +38,8 @@ def e4m3_decode_table() -> np.ndarray:
 
 
 def e4m3_encode(q) -> np.ndarray:
-    """Codes of the E4M3 values nearest to q (ties to even, saturating).  q is taken as fp32 values."""
+    """Codes of the E4M3 values nearest to q (ties to even, saturating): the rounding step of Eq. 1 on that grid.  q is
+    taken as fp32 values."""
     q = np.asarray(q, dtype=np.float32).astype(np.float64)
     sign = np.signbit(q)
     a = np.minimum(np.abs(q), E4M3_MAX)
@@ -55,7 +57,8 @@ def e4m3_encode(q) -> np.ndarray:
 
 
 def quantize_rows(z):
-    """Per-row quantisation: (codes [R, V] uint8, scale [R] fp32) with s = max|z| / 448 (1 for an all-zero row)."""
+    """Per-row quantisation, Eq. 1 with symmetric per-row scaling (Sec. 2.1): (codes [R, V] uint8, scale [R] fp32) with
+    s = max|z| / 448 (1 for an all-zero row)."""
     z = np.asarray(z, dtype=np.float32)
     amax = np.abs(z).max(axis=1).astype(np.float32)
     s = (amax / np.float32(E4M3_MAX)).astype(np.float32)
@@ -65,13 +68,14 @@ def quantize_rows(z):
 
 
 def dequantize_rows(codes, scale):
-    """s * value(code) as fp32 (one correctly rounded fp32 multiplication)."""
+    """The de-quantisation of Eq. 1: s * value(code) as fp32 (one correctly rounded fp32 multiplication)."""
     table = e4m3_decode_table().astype(np.float32)
     return (table[np.asarray(codes)] * np.asarray(scale, dtype=np.float32)[:, None]).astype(np.float32)
 
 
 def rollout_logprob(z, y, valid=None):
-    """log-softmax of the quantise-dequantise round trip of each row, at token y (fp64 from the fp32 z_r)."""
+    """log pi_roll of Alg. 1 ("Sampler-Trainer ratio") for a rollout engine whose logits went through Eq. 1: log-softmax
+    of the quantise-dequantise round trip of each row, at token y (fp64 from the fp32 z_r)."""
     z = np.asarray(z, dtype=np.float32)
     R = z.shape[0]
     valid = np.ones(R, dtype=bool) if valid is None else np.asarray(valid).astype(bool)

@@ -34,7 +34,8 @@ def _f64(x):
 
 
 def logits(hidden, weight):
-    """z[t, v] = <h_t, W[v, :]> ; hidden [R, D], weight [V, D] -> [R, V]."""
+    """The read-out that produces the logits of Alg. 1 ("Compute full-precision log-probs"; the model families of
+    Sec. 4.1): z[t, v] = <h_t, W[v, :]> ; hidden [R, D], weight [V, D] -> [R, V]."""
     h = _f64(hidden)
     w = _f64(weight)
     assert h.ndim == 2 and w.ndim == 2 and h.shape[1] == w.shape[1]
@@ -42,7 +43,8 @@ def logits(hidden, weight):
 
 
 def token_logprob(hidden, weight, y, valid=None, inv_temperature: float = 1.0):
-    """(log pi(y_t), lse_t) per row from hidden states and the output embedding."""
+    """(log pi(y_t), lse_t) per row from hidden states and the output embedding: the log-probs of Alg. 1 ("Compute
+    full-precision log-probs") with the logits formed on the way."""
     z = logits(hidden, weight)
     R = z.shape[0]
     y = np.asarray(y, dtype=np.int64)
@@ -60,7 +62,8 @@ def token_logprob(hidden, weight, y, valid=None, inv_temperature: float = 1.0):
 
 
 def dlogits(hidden, weight, y, g, valid=None, inv_temperature: float = 1.0):
-    """dL/dz for L = -sum_t g_t log pi(y_t): (g_t / T)(softmax - onehot); zero rows where not valid."""
+    """dL/dz for L = -sum_t g_t log pi(y_t), the form Eq. 19 takes once the per-token coefficients g_t are fixed (Alg. 1,
+    "Policy Update"): (g_t / T)(softmax - onehot); zero rows where not valid."""
     z = logits(hidden, weight)
     R = z.shape[0]
     y = np.asarray(y, dtype=np.int64)
@@ -80,7 +83,8 @@ def dlogits(hidden, weight, y, g, valid=None, inv_temperature: float = 1.0):
 
 
 def grads(hidden, weight, y, g, valid=None, inv_temperature: float = 1.0):
-    """(dL/dhidden [R, D], dL/dweight [V, D]) by the chain rule through the read-out."""
+    """(dL/dhidden [R, D], dL/dweight [V, D]): the gradient of Eq. 19 carried through the read-out z = H W^T by the chain
+    rule."""
     dz = dlogits(hidden, weight, y, g, valid, inv_temperature)
     d_hidden = dz @ _f64(weight)
     d_weight = dz.T @ _f64(hidden)
