@@ -76,6 +76,7 @@ typedef enum ais_error {
 /* Bits of the device status word. */
 #define AIS_STATUS_BAD_TOKEN 1   /* evaluated row with token id outside [0, vocab)     */
 #define AIS_STATUS_BAD_CU    2   /* cu_rows not a non-decreasing partition of the rows */
+#define AIS_STATUS_LIVE_OVERFLOW 4 /* ais_lm_head_grad: more rows with a gradient than n_live_max */
 
 /* Hyper-parameters.  ais_params_default() fills in the paper's values:
  * C, delta, gamma, eps_std from App. "AIS hyperparameters"; clip_eps from the
@@ -319,6 +320,14 @@ int ais_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long hidden_strid
  *   coeff       [n_rows] fp32, as written by ais_grpo_row_scale (its g_out: it carries inv_temperature)
  *   chunk_vocab vocabulary entries per chunk, a multiple of 256; 0 selects 8192.  The context workspace grows to
  *               2 * n_rows * chunk_vocab bytes.
+ *   n_live_max  negative, or >= n_rows: every row goes through the recomputation and the GEMMs.  Otherwise a bound
+ *               that the caller vouches for on the number of rows with coeff != 0 (for a masked-diffusion batch:
+ *               the number of evaluated positions, which its loader knows): those rows are gathered on the device
+ *               and recomputation and GEMMs run over n_live_max rows only, so the cost follows the rows that have
+ *               a gradient.  If there are more such rows than n_live_max, the surplus rows are left out (their
+ *               dhidden is 0 and they do not enter dweight) and AIS_STATUS_LIVE_OVERFLOW is set; nothing is read
+ *               or written out of range.  The workspace then holds 2 n_live_max (chunk_vocab + 3 d_model) bytes
+ *               and 9 bytes per row.
  *   dhidden_out [n_rows, d_model] fp32, contiguous; dweight_out [vocab, d_model] fp32, contiguous; both are
  *               overwritten.
  * Errors: as ais_lm_head_logprob; d_model not a multiple of 32 or chunk_vocab not a multiple of 256
@@ -326,8 +335,8 @@ int ais_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long hidden_strid
 int ais_lm_head_grad(ais_ctx* ctx, const void* hidden, long long hidden_stride, const void* weight,
                      long long weight_stride, ais_dtype dtype, long long n_rows, long long d_model,
                      long long vocab, const int* token_ids, const float* lse, const float* logp,
-                     const float* coeff, float inv_temperature, long long chunk_vocab, float* dhidden_out,
-                     float* dweight_out);
+                     const float* coeff, float inv_temperature, long long chunk_vocab, long long n_live_max,
+                     float* dhidden_out, float* dweight_out);
 
 /* ---- measurement helpers -------------------------------------------------------------------- */
 

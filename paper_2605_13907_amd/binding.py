@@ -21,6 +21,7 @@ AIS_K_LOGPROB, AIS_K_DLOGITS, AIS_K_COPY, AIS_K_FP8_QUANT, AIS_K_FP8_DEQUANT, AI
 AIS_K_FUSED = 6
 AIS_K_LM_HEAD = 7
 AIS_K_LM_HEAD_GRAD = 8
+AIS_STATUS_LIVE_OVERFLOW = 4
 STATUS_BAD_TOKEN, STATUS_BAD_CU = 1, 2
 
 ERRORS = {
@@ -79,7 +80,7 @@ SYMBOLS = {
     "ais_fp8_dequantize_rows": (_I, [_P, _P, _LL, _P, _LL, _LL, _P, _I, _LL]),
     "ais_fp8_rollout_logprob": (_I, [_P, _P, _I, _LL, _LL, _LL, _P, _P, _P]),
     "ais_lm_head_logprob": (_I, [_P, _P, _LL, _P, _LL, _I, _LL, _LL, _LL, _P, _P, _F, _P, _P]),
-    "ais_lm_head_grad": (_I, [_P, _P, _LL, _P, _LL, _I, _LL, _LL, _LL, _P, _P, _P, _P, _F, _LL, _P, _P]),
+    "ais_lm_head_grad": (_I, [_P, _P, _LL, _P, _LL, _I, _LL, _LL, _LL, _P, _P, _P, _P, _F, _LL, _LL, _P, _P]),
     "ais_profile": (_I, [_P, _I]),
     "ais_profile_read": (_I, [_P, _I, C.POINTER(_F), C.POINTER(_I)]),
     "ais_copy": (_I, [_P, _P, _P, _LL]),
@@ -403,10 +404,11 @@ class AisContext:
         return logp, lse
 
     def lm_head_grad(self, hidden, weight, token_ids, lse, logp, coeff, inv_temperature: float = 1.0,
-                     chunk_vocab: int = 0):
+                     chunk_vocab: int = 0, n_live_max: int = -1):
         """-> (dhidden [R, D] fp32, dweight [V, D] fp32): gradient of the loss w.r.t. the read-out's operands from the
         per-row coefficient (the g of grpo_row_scale) and the lse / logp of lm_head_logprob; the [R, V] logits and
-        their gradient never exist as a whole.  See ais_lm_head_grad in include/ais.h."""
+        their gradient never exist as a whole.  n_live_max: a bound the caller vouches for on the number of rows with a
+        non-zero coefficient (-1: none): the work then follows that number.  See ais_lm_head_grad in include/ais.h."""
         for name, t in (("hidden", hidden), ("weight", weight)):
             if t.dim() != 2 or t.stride(1) != 1:
                 raise ValueError(f"{name} must be 2-D with unit stride along d_model")
@@ -426,8 +428,8 @@ class AisContext:
         rc = self._lib.ais_lm_head_grad(
             self._h, C.c_void_p(hidden.data_ptr()), hidden.stride(0) if n_rows > 1 else max(d_model, hidden.stride(0)),
             C.c_void_p(weight.data_ptr()), weight.stride(0) if vocab > 1 else max(d_model, weight.stride(0)),
-            AIS_BF16, n_rows, d_model, vocab, *ptrs, float(inv_temperature), int(chunk_vocab), _ptr(dhidden),
-            _ptr(dweight))
+            AIS_BF16, n_rows, d_model, vocab, *ptrs, float(inv_temperature), int(chunk_vocab), int(n_live_max),
+            _ptr(dhidden), _ptr(dweight))
         if rc != 0:
             raise AisError(rc, "ais_lm_head_grad")
         return dhidden, dweight

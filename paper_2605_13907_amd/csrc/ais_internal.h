@@ -145,7 +145,14 @@ int launch_fp8_rollout_logprob(ais_ctx* ctx, const void* logits, ais_dtype dtype
 int launch_lm_head_dlogits_chunk(ais_ctx* ctx, const void* hidden, long long ld_h, const void* weight,
                                  long long ld_w, long long n_rows, int d_model, int vocab, int y_off,
                                  const int* token_ids, const float* lse, const float* logp, const float* coeff,
-                                 float inv_temperature, void* dev_plan, void* ds, long long ds_stride);
+                                 float inv_temperature, void* dev_plan, void* ds, long long ds_stride,
+                                 const unsigned char* live_mask, int* row_index, int* row_pos, int n_cap);
+int launch_lm_live_mask(ais_ctx* ctx, const float* coeff, long long n_rows, unsigned char* mask);
+int launch_lm_gather_rows(ais_ctx* ctx, const void* hidden, long long ld_h, long long n_rows, int d_model,
+                          const unsigned char* live_mask, int* row_index, int* row_pos, void* dev_plan, int n_cap,
+                          void* gathered);
+int launch_lm_scatter_rows(ais_ctx* ctx, const float* gathered, const int* row_pos, long long n_rows, int d_model,
+                           float* out);
 int launch_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long ld_h, const void* weight, long long ld_w,
                            long long n_rows, int d_model, int vocab, const int* token_ids,
                            const unsigned char* valid, float inv_temperature, const LmHeadPlan& plan,

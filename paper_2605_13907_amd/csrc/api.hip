@@ -504,7 +504,8 @@ int ais_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long hidden_strid
 int ais_lm_head_grad(ais_ctx* ctx, const void* hidden, long long hidden_stride, const void* weight,
                      long long weight_stride, ais_dtype dtype, long long n_rows, long long d_model, long long vocab,
                      const int* token_ids, const float* lse, const float* logp, const float* coeff,
-                     float inv_temperature, long long chunk_vocab, float* dhidden_out, float* dweight_out) {
+                     float inv_temperature, long long chunk_vocab, long long n_live_max, float* dhidden_out,
+                     float* dweight_out) {
   if (dtype != AIS_BF16) return AIS_ERR_DTYPE;
   if (n_rows < 0 || n_rows > 0x7fffffffLL - 256) return AIS_ERR_SIZE;
   if (vocab < 1 || vocab > 0x7fffffffLL - 256) return AIS_ERR_SIZE;
@@ -530,13 +531,45 @@ int ais_lm_head_grad(ais_ctx* ctx, const void* hidden, long long hidden_stride, 
     return hip_fail(ctx, hipGetLastError());
   }
   if (chunk_vocab > ((vocab + 255) / 256) * 256) chunk_vocab = ((vocab + 255) / 256) * 256;
-  // workspace: the chunk's dlogits, then the device-side decomposition of the recompute kernel
-  const size_t ds_bytes = ((size_t)n_rows * (size_t)chunk_vocab * 2 + 255) & ~size_t(255);
-  int rc = ensure_workspace(ctx, ds_bytes + 256);
+  const bool gather = n_live_max >= 0 && n_live_max < n_rows;
+  const long long m_rows = gather ? n_live_max : n_rows;       // rows that the recomputation and the GEMMs cover
+  if (m_rows == 0) {                    // the caller vouches that no row has a gradient
+    zero_fill_kernel<<<(unsigned)std::min<size_t>(((size_t)vocab * d_model + 255) / 256, (size_t)ctx->n_cus * 8), 256, 0,
+                       ctx->stream>>>(dweight_out, (size_t)vocab * (size_t)d_model);
+    zero_fill_kernel<<<(unsigned)std::min<size_t>(((size_t)n_rows * d_model + 255) / 256, (size_t)ctx->n_cus * 8), 256, 0,
+                       ctx->stream>>>(dhidden_out, (size_t)n_rows * (size_t)d_model);
+    return hip_fail(ctx, hipGetLastError());
+  }
+  // workspace: the chunk's dlogits, the device-side decomposition of the recompute kernel and, with a row list, the
+  // mask, the list, its inverse, the gathered hidden states and their gradient
+  auto up = [](size_t b) { return (b + 255) & ~size_t(255); };
+  const size_t ds_bytes = up((size_t)m_rows * (size_t)chunk_vocab * 2);
+  const size_t plan_bytes = 256;
+  const size_t mask_bytes = gather ? up((size_t)n_rows) : 0;
+  const size_t list_bytes = gather ? up((size_t)n_rows * 4) : 0;
+  const size_t hg_bytes = gather ? up((size_t)m_rows * (size_t)d_model * 2) : 0;
+  const size_t dhg_bytes = gather ? up((size_t)m_rows * (size_t)d_model * 4) : 0;
+  int rc = ensure_workspace(ctx, ds_bytes + plan_bytes + mask_bytes + 2 * list_bytes + hg_bytes + dhg_bytes);
   if (rc != AIS_OK) return rc;
   ctx->plan.valid = false;             // the chunk's dlogits overwrite whatever tiling the workspace held
   char* ds = static_cast<char*>(ctx->ws);
   void* dev_plan = ds + ds_bytes;
+  unsigned char* live_mask = gather ? reinterpret_cast<unsigned char*>(ds + ds_bytes + plan_bytes) : nullptr;
+  int* row_index = gather ? reinterpret_cast<int*>(ds + ds_bytes + plan_bytes + mask_bytes) : nullptr;
+  int* row_pos = gather ? reinterpret_cast<int*>(ds + ds_bytes + plan_bytes + mask_bytes + list_bytes) : nullptr;
+  char* h_gathered = ds + ds_bytes + plan_bytes + mask_bytes + 2 * list_bytes;
+  float* dh_gathered = reinterpret_cast<float*>(h_gathered + hg_bytes);
+  if (gather) {
+    rc = launch_lm_live_mask(ctx, coeff, n_rows, live_mask);
+    if (rc == AIS_OK)
+      rc = launch_lm_gather_rows(ctx, hidden, hidden_stride, n_rows, (int)d_model, live_mask, row_index, row_pos, dev_plan,
+                                 (int)m_rows, h_gathered);
+    if (rc != AIS_OK) return rc;
+  }
+  // operands of the two GEMMs: the hidden states they read and the gradient they write, with their pitches
+  const void* h_gemm = gather ? static_cast<const void*>(h_gathered) : hidden;
+  const long long h_gemm_stride = gather ? d_model : hidden_stride;
+  float* dh_gemm = gather ? dh_gathered : dhidden_out;
   if (ctx->blas == nullptr) {
     rocblas_handle h = nullptr;
     if (rocblas_create_handle(&h) != rocblas_status_success) return AIS_ERR_HIP;
@@ -552,27 +585,28 @@ int ais_lm_head_grad(ais_ctx* ctx, const void* hidden, long long hidden_stride, 
     const void* w_chunk = w_base + (size_t)v0 * (size_t)weight_stride * 2;
     rc = launch_lm_head_dlogits_chunk(ctx, hidden, hidden_stride, w_chunk, weight_stride, n_rows, (int)d_model, width,
                                       (int)v0, token_ids, lse, logp, coeff, inv_temperature, dev_plan, ds,
-                                      chunk_vocab);
+                                      chunk_vocab, live_mask, row_index, row_pos, (int)m_rows);
     if (rc != AIS_OK) return rc;
     // The library is column-major; a row-major [r, c] matrix with pitch p is its column-major [c, r] transpose
     // with leading dimension p.
-    // dhidden[n_rows, D] (+)= ds[n_rows, width] weight_chunk[width, D]:   C^T[D, n_rows] = W_c^T[D, width] ds^T[width, n_rows]
+    // dhidden[m_rows, D] (+)= ds[m_rows, width] weight_chunk[width, D]:   C^T[D, m_rows] = W_c^T[D, width] ds^T[width, m_rows]
     rocblas_status st = rocblas_gemm_ex(
-        blas, rocblas_operation_none, rocblas_operation_none, (rocblas_int)d_model, (rocblas_int)n_rows, width, &one,
+        blas, rocblas_operation_none, rocblas_operation_none, (rocblas_int)d_model, (rocblas_int)m_rows, width, &one,
         w_chunk, rocblas_datatype_bf16_r, (rocblas_int)weight_stride, ds, rocblas_datatype_bf16_r,
-        (rocblas_int)chunk_vocab, v0 == 0 ? &zero : &one, dhidden_out, rocblas_datatype_f32_r, (rocblas_int)d_model,
-        dhidden_out, rocblas_datatype_f32_r, (rocblas_int)d_model, rocblas_datatype_f32_r, rocblas_gemm_algo_standard,
+        (rocblas_int)chunk_vocab, v0 == 0 ? &zero : &one, dh_gemm, rocblas_datatype_f32_r, (rocblas_int)d_model,
+        dh_gemm, rocblas_datatype_f32_r, (rocblas_int)d_model, rocblas_datatype_f32_r, rocblas_gemm_algo_standard,
         0, 0);
     if (st != rocblas_status_success) return AIS_ERR_HIP;
-    // dweight_chunk[width, D] = ds^T[width, n_rows] hidden[n_rows, D]:   C^T[D, width] = H^T[D, n_rows] ds[n_rows, width]
+    // dweight_chunk[width, D] = ds^T[width, m_rows] hidden[m_rows, D]:   C^T[D, width] = H^T[D, m_rows] ds[m_rows, width]
     float* dw_chunk = dweight_out + (size_t)v0 * (size_t)d_model;
     st = rocblas_gemm_ex(blas, rocblas_operation_none, rocblas_operation_transpose, (rocblas_int)d_model, width,
-                         (rocblas_int)n_rows, &one, hidden, rocblas_datatype_bf16_r, (rocblas_int)hidden_stride, ds,
+                         (rocblas_int)m_rows, &one, h_gemm, rocblas_datatype_bf16_r, (rocblas_int)h_gemm_stride, ds,
                          rocblas_datatype_bf16_r, (rocblas_int)chunk_vocab, &zero, dw_chunk, rocblas_datatype_f32_r,
                          (rocblas_int)d_model, dw_chunk, rocblas_datatype_f32_r, (rocblas_int)d_model,
                          rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0);
     if (st != rocblas_status_success) return AIS_ERR_HIP;
   }
+  if (gather) return launch_lm_scatter_rows(ctx, dh_gathered, row_pos, n_rows, (int)d_model, dhidden_out);
   return AIS_OK;
 }
 

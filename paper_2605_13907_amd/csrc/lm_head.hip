@@ -261,6 +261,7 @@ struct LmGradArgs {
   bf16_t* ds;              // [n_rows, ds_stride]  coeff (softmax - onehot) over this chunk of the vocabulary
   long long ds_stride;     // elements, a multiple of 4
   int y_off;               // first vocabulary entry of the chunk: token ids are global, tile indices local
+  int compact;             // != 0: row p of ds belongs to the p-th listed row (LmRows::index), not to source row p
 };
 
 // Per-lane state of the gradient variant: for each of the lane's two token columns the row it writes to, the
@@ -282,7 +283,7 @@ struct LmGrad {
       dy[j] = 0.f;
       if (tok < it.n_eval) {
         const int r = rows.row(tok, it.n_eval);
-        row[j] = r;
+        row[j] = ga.compact ? tok : r;
         c[j] = ga.coeff[r];
         if (c[j] != 0.f) {                  // rows without gradient: lse may be 0 there, and nothing is exponentiated
           const int id = token_ids[r] - ga.y_off;
@@ -875,10 +876,12 @@ __global__ __launch_bounds__(kLmThreads) void lm_head_staged_kernel(
 // One workgroup, before the main kernel.  With a mask it lists the rows to evaluate (index[p] = p-th row with
 // valid != 0, pos[n] = position of row n in that list or -1; each thread owns a contiguous run of rows); in
 // both cases thread 0 then decides the decomposition for the number of evaluated rows.
+// n_cap >= 0: the list holds at most n_cap rows; further rows are dropped (pos = -1) and reported in *status.
 __global__ __launch_bounds__(1024) void lm_head_setup_kernel(const unsigned char* __restrict__ valid, int n_rows,
                                                              int n_vtiles, int n_cus, int max_items, int tb_group,
                                                              int* __restrict__ index, int* __restrict__ pos,
-                                                             LmDevPlan* __restrict__ plan) {
+                                                             LmDevPlan* __restrict__ plan, int n_cap = -1,
+                                                             int* __restrict__ status = nullptr) {
   __shared__ int run_start[1024];
   __shared__ int total;
   const int tid = threadIdx.x;
@@ -899,15 +902,26 @@ __global__ __launch_bounds__(1024) void lm_head_setup_kernel(const unsigned char
       total = run;
     }
     __syncthreads();
+    const int cap = n_cap >= 0 ? n_cap : n_rows;
     int p = run_start[tid];
     for (int n = r0; n < r1; ++n) {
       if (valid[n] != 0) {
-        index[p] = n;
-        pos[n] = p++;
+        if (p < cap) {
+          index[p] = n;
+          pos[n] = p;
+        } else {
+          pos[n] = -1;
+        }
+        ++p;
       } else {
         pos[n] = -1;
       }
     }
+    if (tid == 0 && total > cap) {
+      total = cap;
+      if (status != nullptr) atomicOr(status, AIS_STATUS_LIVE_OVERFLOW);
+    }
+    // (total is read below by thread 0 only)
   } else if (tid == 0) {
     total = n_rows;
   }
@@ -955,6 +969,46 @@ __global__ __launch_bounds__(256) void lm_head_merge_kernel(const float* __restr
     logp_out[n] = 0.f;
     atomicOr(status, AIS_STATUS_BAD_TOKEN);
   }
+}
+
+// ---- rows that take part in the gradient call, gathered ------------------------------------------------------
+__global__ __launch_bounds__(256) void lm_live_mask_kernel(const float* __restrict__ coeff, int n_rows,
+                                                           unsigned char* __restrict__ mask) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n < n_rows) mask[n] = coeff[n] != 0.f;
+}
+
+// out[p, :] = hidden[index[p], :] for the listed rows, zeros for p in [n_eval, n_cap).  One workgroup per row.
+__global__ __launch_bounds__(256) void lm_gather_rows_kernel(const bf16_t* __restrict__ hidden, long long ld_h,
+                                                             const int* __restrict__ index,
+                                                             const LmDevPlan* __restrict__ plan, int d_model,
+                                                             bf16_t* __restrict__ out) {
+  const int p = blockIdx.x;
+  const bool live = p < plan->n_eval;
+  const u32x4* src = reinterpret_cast<const u32x4*>(hidden + (live ? (long long)index[p] * ld_h : 0));
+  u32x4* dst = reinterpret_cast<u32x4*>(out + (long long)p * d_model);
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  for (int c = threadIdx.x; c < d_model / 8; c += 256) dst[c] = live ? src[c] : zero;
+}
+
+// Rows [n_eval, n_cap) of a chunk of dlogits are nobody's: zeros, so that the two GEMMs can run over n_cap rows.
+__global__ __launch_bounds__(256) void lm_zero_tail_rows_kernel(bf16_t* __restrict__ ds, long long ds_stride,
+                                                                int width, const LmDevPlan* __restrict__ plan) {
+  const int p = plan->n_eval + blockIdx.x;                      // the grid covers n_cap rows; only the tail works
+  if (p >= (int)gridDim.x) return;
+  bf16_t* row = ds + (long long)p * ds_stride;
+  for (int v = threadIdx.x; v < width; v += 256) row[v] = 0;
+}
+
+// dhidden[n, :] = gathered[pos[n], :] for the listed rows, zeros for the others.  One workgroup per row.
+__global__ __launch_bounds__(256) void lm_scatter_rows_kernel(const float* __restrict__ gathered,
+                                                              const int* __restrict__ pos, int d_model,
+                                                              float* __restrict__ out) {
+  const int n = blockIdx.x;
+  const int p = pos[n];
+  const float4* src = reinterpret_cast<const float4*>(gathered + (long long)(p < 0 ? 0 : p) * d_model);
+  float4* dst = reinterpret_cast<float4*>(out + (long long)n * d_model);
+  for (int c = threadIdx.x; c < d_model / 4; c += 256) dst[c] = p < 0 ? make_float4(0.f, 0.f, 0.f, 0.f) : src[c];
 }
 
 }  // namespace
@@ -1023,10 +1077,13 @@ int launch_lm_head_logprob(ais_ctx* ctx, const void* hidden, long long ld_h, con
 // dlogits of one chunk of the vocabulary, from hidden states and the chunk's rows of the output embedding, into
 // ds[n_rows, ds_stride] (bf16).  `weight` points at the chunk's first row, `vocab` is the chunk's width, `y_off` its
 // first vocabulary entry.  Every row is processed (rows whose coefficient is 0 come out as zeros).
+// With a list (live_mask != nullptr: the rows with a gradient, at most n_cap of them) row p of ds belongs to the p-th
+// listed row and rows up to n_cap - 1 are written (zeros past the end of the list).
 int launch_lm_head_dlogits_chunk(ais_ctx* ctx, const void* hidden, long long ld_h, const void* weight,
                                  long long ld_w, long long n_rows, int d_model, int vocab, int y_off,
                                  const int* token_ids, const float* lse, const float* logp, const float* coeff,
-                                 float inv_temperature, void* dev_plan, void* ds, long long ds_stride) {
+                                 float inv_temperature, void* dev_plan, void* ds, long long ds_stride,
+                                 const unsigned char* live_mask, int* row_index, int* row_pos, int n_cap) {
   constexpr int kStreamLds = AIS_LM_STAGES * kStStageBytes;
   static std::once_flag once[kMaxDevices], once64[kMaxDevices];
   static bool ok[kMaxDevices], ok64[kMaxDevices];
@@ -1037,12 +1094,13 @@ int launch_lm_head_dlogits_chunk(ais_ctx* ctx, const void* hidden, long long ld_
   const LmHeadPlan plan = lm_head_plan(n_rows, vocab, ctx->n_cus);
   const int max_items = ((plan.n_tblocks * plan.n_chunks + 7) / 8) * 8;
   LmDevPlan* dplan = static_cast<LmDevPlan*>(dev_plan);
-  lm_head_setup_kernel<<<1, 1024, 0, ctx->stream>>>(nullptr, (int)n_rows, plan.n_vtiles, ctx->n_cus, max_items,
-                                                    kLmTokenBlockGroup, nullptr, nullptr, dplan);
+  lm_head_setup_kernel<<<1, 1024, 0, ctx->stream>>>(live_mask, (int)n_rows, plan.n_vtiles, ctx->n_cus, max_items,
+                                                    kLmTokenBlockGroup, row_index, row_pos, dplan,
+                                                    live_mask != nullptr ? n_cap : -1, ctx->status_dev);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail(ctx, e);
-  LmRows rows{nullptr, (int)n_rows};
-  LmGradArgs ga{lse, logp, coeff, static_cast<bf16_t*>(ds), ds_stride, y_off};
+  LmRows rows{live_mask != nullptr ? row_index : nullptr, (int)n_rows};
+  LmGradArgs ga{lse, logp, coeff, static_cast<bf16_t*>(ds), ds_stride, y_off, live_mask != nullptr ? 1 : 0};
   {
     ScopedTimer timer(ctx, AIS_K_LM_HEAD_GRAD);
     if (d_model % kS64K == 0)
@@ -1054,6 +1112,37 @@ int launch_lm_head_dlogits_chunk(ais_ctx* ctx, const void* hidden, long long ld_
           static_cast<const bf16_t*>(hidden), ld_h, static_cast<const bf16_t*>(weight), ld_w, rows, dplan, d_model,
           vocab, token_ids, inv_temperature * kLog2e, plan.n_vtiles, nullptr, nullptr, nullptr, ga);
   }
+  e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  if (live_mask != nullptr && n_cap > 0)
+    lm_zero_tail_rows_kernel<<<(unsigned)n_cap, 256, 0, ctx->stream>>>(static_cast<bf16_t*>(ds), ds_stride, vocab,
+                                                                       dplan);
+  return hip_fail(ctx, hipGetLastError());
+}
+
+int launch_lm_live_mask(ais_ctx* ctx, const float* coeff, long long n_rows, unsigned char* mask) {
+  lm_live_mask_kernel<<<(unsigned)((n_rows + 255) / 256), 256, 0, ctx->stream>>>(coeff, (int)n_rows, mask);
+  return hip_fail(ctx, hipGetLastError());
+}
+
+// The list and the plan for `n_rows` rows with the mask, once (the chunk launches rebuild the plan for their width).
+int launch_lm_gather_rows(ais_ctx* ctx, const void* hidden, long long ld_h, long long n_rows, int d_model,
+                          const unsigned char* live_mask, int* row_index, int* row_pos, void* dev_plan, int n_cap,
+                          void* gathered) {
+  LmDevPlan* dplan = static_cast<LmDevPlan*>(dev_plan);
+  lm_head_setup_kernel<<<1, 1024, 0, ctx->stream>>>(live_mask, (int)n_rows, 1, ctx->n_cus, 1 << 30,
+                                                    kLmTokenBlockGroup, row_index, row_pos, dplan, n_cap,
+                                                    ctx->status_dev);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(ctx, e);
+  lm_gather_rows_kernel<<<(unsigned)n_cap, 256, 0, ctx->stream>>>(static_cast<const bf16_t*>(hidden), ld_h, row_index,
+                                                                  dplan, d_model, static_cast<bf16_t*>(gathered));
+  return hip_fail(ctx, hipGetLastError());
+}
+
+int launch_lm_scatter_rows(ais_ctx* ctx, const float* gathered, const int* row_pos, long long n_rows, int d_model,
+                           float* out) {
+  lm_scatter_rows_kernel<<<(unsigned)n_rows, 256, 0, ctx->stream>>>(gathered, row_pos, d_model, out);
   return hip_fail(ctx, hipGetLastError());
 }
 

@@ -342,11 +342,11 @@ def test_lm_head_grad_argument_checks():
 
     def call(**kw):
         a = dict(ctx=None, hidden=FAKE, ld_h=64, weight=FAKE, ld_w=64, dtype=B.AIS_BF16, n_rows=4, d=64, vocab=100,
-                 tok=FAKE, lse=FAKE, logp=FAKE, coeff=FAKE, inv_t=1.0, chunk=0, dh=FAKE, dw=FAKE)
+                 tok=FAKE, lse=FAKE, logp=FAKE, coeff=FAKE, inv_t=1.0, chunk=0, live=-1, dh=FAKE, dw=FAKE)
         a.update(kw)
         return lib.ais_lm_head_grad(a["ctx"], a["hidden"], a["ld_h"], a["weight"], a["ld_w"], a["dtype"], a["n_rows"],
                                     a["d"], a["vocab"], a["tok"], a["lse"], a["logp"], a["coeff"], a["inv_t"],
-                                    a["chunk"], a["dh"], a["dw"])
+                                    a["chunk"], a["live"], a["dh"], a["dw"])
 
     assert call() == -1                                   # everything fine except the NULL context
     assert call(dtype=B.AIS_F32) == -7
@@ -357,6 +357,7 @@ def test_lm_head_grad_argument_checks():
     assert call(weight=None) == -1 and call(dw=None) == -1 and call(lse=None) == -1 and call(coeff=None) == -1
     assert call(hidden=C.c_void_p(0x1008)) == -4 and call(ld_w=68) == -4
     assert call(inv_t=0.0) == -5 and call(inv_t=float("inf")) == -5
+    assert call(live=0) == -1 and call(live=3) == -1 and call(live=10 ** 12) == -1      # any bound is a valid argument
 
 
 def test_binding_rejects_host_tensors_before_any_launch():

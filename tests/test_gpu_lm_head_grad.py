@@ -226,3 +226,86 @@ def test_empty_batch(ctx):
     torch.cuda.synchronize()
     assert dh.shape == (0, D) and dw.shape == (V, D) and not bool(dw.any())
     assert ctx.status() == 0
+
+
+def _live_case(ctx, R, D, V, seed, live_share, chunk):
+    hidden, weight, y, _ = make(R, D, V, seed=seed)
+    rng = np.random.default_rng(seed)
+    g = (rng.normal(0, 1.0, size=R) * 1e-2).astype(np.float32)
+    g[rng.random(R) >= live_share] = 0.0
+    logp, lse = ctx.lm_head_logprob(hidden, weight, y)
+    coeff = torch.from_numpy(g).cuda()
+    return hidden, weight, y, logp, lse, coeff, int((g != 0).sum())
+
+
+@pytest.mark.parametrize("R,D,V,chunk,live_share", [(700, 64, 1500, 512, 0.5), (1300, 128, 3000, 1024, 0.1),
+                                                    (513, 96, 777, 256, 0.9), (300, 64, 600, 256, 0.0)])
+def test_row_bound_gives_the_same_gradients(ctx, R, D, V, chunk, live_share):
+    """With a bound on the rows that have a gradient the call gathers them and runs over that many rows: same
+    gradients as without (to the rounding of a different summation order in the GEMMs), for the exact count, for a
+    loose bound, and for a bound of zero rows when no row is live."""
+    hidden, weight, y, logp, lse, coeff, n_live = _live_case(ctx, R, D, V, R + V, live_share, chunk)
+    ref_h, ref_w = ctx.lm_head_grad(hidden, weight, y, lse, logp, coeff, 1.0, chunk)
+    for bound in sorted({n_live, min(R - 1, n_live + 37), min(R - 1, 2 * n_live + 1)}):
+        dh, dw = ctx.lm_head_grad(hidden, weight, y, lse, logp, coeff, 1.0, chunk, n_live_max=bound)
+        torch.cuda.synchronize()
+        assert ctx.status() == 0, f"bound {bound} of {n_live} live rows"
+        live = coeff != 0
+        assert not bool(dh[~live].any())
+        # the same bf16 dlogits enter both routes; only the order of the fp32 sums differs
+        scale_h = ref_h.abs().max().item() + 1e-30
+        scale_w = ref_w.abs().max().item() + 1e-30
+        assert (dh - ref_h).abs().max().item() <= 2e-5 * scale_h, bound
+        assert (dw - ref_w).abs().max().item() <= 2e-5 * scale_w, bound
+
+
+def test_row_bound_against_the_oracle(ctx):
+    """The gathered route on its own against the fp64 oracle, at the tolerance of the plain route."""
+    R, D, V, chunk = 900, 128, 2500, 512
+    hidden, weight, y, logp, lse, coeff, n_live = _live_case(ctx, R, D, V, 91, 0.4, chunk)
+    dh, dw = ctx.lm_head_grad(hidden, weight, y, lse, logp, coeff, 1.0, chunk, n_live_max=n_live)
+    torch.cuda.synchronize()
+    assert ctx.status() == 0
+    h64, w64 = f64(hidden), f64(weight)
+    g = coeff.cpu().numpy().astype(np.float64)
+    dz = L.dlogits(h64, w64, y.cpu().numpy(), g, g != 0, 1.0)
+    tol_dz = dz_tolerance(dz, None, None, True)
+    err_h, err_w = np.abs(f64(dh) - dz @ w64), np.abs(f64(dw) - dz.T @ h64)
+    assert np.all(err_h <= tol_dz @ np.abs(w64) + 1e-30) and np.all(err_w <= tol_dz.T @ np.abs(h64) + 1e-30)
+
+
+def test_row_bound_too_small_is_reported_and_stays_in_bounds(ctx):
+    """More live rows than the bound: the status word says so, the rows that fit get their gradient, the others
+    zeros; every value is finite."""
+    R, D, V, chunk = 640, 64, 1200, 256
+    hidden, weight, y, logp, lse, coeff, n_live = _live_case(ctx, R, D, V, 17, 0.6, chunk)
+    bound = n_live // 2
+    dh, dw = ctx.lm_head_grad(hidden, weight, y, lse, logp, coeff, 1.0, chunk, n_live_max=bound)
+    torch.cuda.synchronize()
+    assert ctx.status() == B.AIS_STATUS_LIVE_OVERFLOW
+    assert torch.isfinite(dh).all() and torch.isfinite(dw).all()
+    live_rows = torch.nonzero(coeff != 0).flatten()
+    kept, dropped = live_rows[:bound], live_rows[bound:]
+    assert not bool(dh[dropped].any())
+    ref_h, _ = ctx.lm_head_grad(hidden, weight, y, lse, logp, coeff, 1.0, chunk)
+    assert (dh[kept] - ref_h[kept]).abs().max().item() <= 2e-5 * ref_h.abs().max().item()
+    assert ctx.status() == 0
+
+
+def test_row_bound_on_the_masked_workload(ctx):
+    """The LLaDA-shaped read-out (about half of the positions evaluated) at full width on 2,048 rows: the bound is
+    the number of evaluated positions, as the batch's loader knows it."""
+    batch = W.generate_readout(W.config(3), device="cuda", n_rows=2048)
+    R = batch.hidden.shape[0]
+    logp, lse = ctx.lm_head_logprob(batch.hidden, batch.weight, batch.token_ids, batch.valid)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(3)
+    coeff = torch.randn(R, device="cuda", generator=gen) * 1e-4 * (batch.valid != 0)
+    n_valid = int((batch.valid != 0).sum().item())
+    assert 0 < n_valid < R
+    ref_h, ref_w = ctx.lm_head_grad(batch.hidden, batch.weight, batch.token_ids, lse, logp, coeff)
+    dh, dw = ctx.lm_head_grad(batch.hidden, batch.weight, batch.token_ids, lse, logp, coeff, n_live_max=n_valid)
+    torch.cuda.synchronize()
+    assert ctx.status() == 0
+    assert (dh - ref_h).abs().max().item() <= 2e-5 * ref_h.abs().max().item()
+    assert (dw - ref_w).abs().max().item() <= 2e-5 * ref_w.abs().max().item()
